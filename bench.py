@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer forward (Algorithm 1 without the all-reduce) on one MI355X.
+
+A "step" is one moe_layer_forward call: gate, permutation, slice, both grouped expert GEMMs and the
+combine, over one batch of synthetic tokens already resident in HBM.  The default workload is the
+headline configuration (T=8192, d=2048, F=8192, E=8, top-1, bf16).
+
+Prints ONE JSON line: layer tokens/s as `value`, a `roofline` object for the dominant kernel (the
+GeLU grouped GEMM) timed with HIP events recorded inside the timed region, per-stage timings, and a
+`cpu_baseline` object: the fp64 oracle timed on the host cores on a bounded token sample.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(lc, inp, sample_tokens):
+    """The oracle as it stands, on the first `sample_tokens` tokens of the same workload."""
+    from oracle import ppmoe_oracle as O
+    from paper_2304_11414_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    mv = synth.math_views(inp)
+    xs = inp["x"][:sample_tokens]
+    t0 = time.perf_counter()
+    O.layer_forward(xs, mv["Wg"], inp["bias"], mv["W1"], mv["W2"], E=lc.E, k=lc.top_k,
+                    local_begin=lc.local_begin, local_count=lc.n_local,
+                    capacity_factor=lc.capacity_factor, renorm=lc.renorm_topk)
+    dt = time.perf_counter() - t0
+    return {"value": xs.shape[0] / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"whole layer (numpy fp64) on the first {xs.shape[0]} of {lc.T} tokens, "
+                      f"all {lc.n_local} local experts' weights, {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into synth.CONFIGS (1 = headline)")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "--gpus must be 1")
+
+    import torch
+    from paper_2304_11414_amd import binding as B
+    from paper_2304_11414_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.load_library()
+    lc = synth.CONFIGS[args.config]
+    log(f"[bench] workload {lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
+        f"top_k={lc.top_k} cf={lc.capacity_factor} {lc.in_dtype}->{lc.out_dtype}")
+    inp = synth.make_inputs(lc)
+    cfg = B.config_from(lc)
+    tdt = torch.bfloat16 if lc.in_dtype == "bf16" else torch.float32
+    odt = torch.bfloat16 if lc.out_dtype == "bf16" else torch.float32
+    dev = {k: (torch.from_numpy(v).cuda().to(tdt) if k != "bias" else torch.from_numpy(v).cuda())
+           for k, v in inp.items() if v is not None}
+    bias = dev.get("bias")
+    ws = torch.empty(B.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    out = torch.empty((lc.T, lc.d), dtype=odt, device="cuda")
+
+    def step(events=None):
+        B.moe_layer_forward(cfg, dev["x"], dev["Wg_t"], bias, dev["W1_t"], dev["W2_t"], out, ws,
+                            stage_events=events)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    events = [[B.moe_event_create() for _ in range(B.MOE_NUM_STAGES + 1)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+
+    stage_ms = np.zeros(B.MOE_NUM_STAGES)
+    for i in range(K):
+        for s in range(B.MOE_NUM_STAGES):
+            stage_ms[s] += B.moe_event_elapsed_ms(events[i][s], events[i][s + 1])
+    stage_ms /= K
+    ev_total = float(np.mean([B.moe_event_elapsed_ms(e[0], e[-1]) for e in events]))
+    for e in events:
+        for h in e:
+            B.moe_event_destroy(h)
+
+    views = B.workspace_views(cfg, ws)
+    counts = views["counts"].cpu().numpy()
+    A = int(views["offsets"][-1].item())
+    eb = 2 if lc.in_dtype == "bf16" else 4
+    ob = 2 if lc.out_dtype == "bf16" else 4
+    k = lc.top_k
+    flops_up = 2.0 * A * lc.d * lc.F
+    flops_dn = 2.0 * A * lc.F * lc.d
+    flops_router = 2.0 * lc.T * lc.d * lc.E
+    bytes_gate = lc.T * lc.d * eb + lc.E * lc.d * eb + 8 * k * lc.T
+    bytes_slice = A * (2 * lc.d * eb + 4)
+    bytes_combine = A * lc.d * eb + lc.T * (lc.d * ob + 8 * k)
+    names = B.STAGE_NAMES
+    st = dict(zip(names, stage_ms.tolist()))
+    tflops_up = flops_up / (st["ffn_up"] * 1e-3) / 1e12
+    tflops_dn = flops_dn / (st["ffn_down"] * 1e-3) / 1e12
+    detail = {
+        "stage_ms": {n: round(v, 5) for n, v in st.items()},
+        "event_ms_per_step": round(ev_total, 5),
+        "kept_rows": A, "expert_rows": counts.tolist(),
+        "drop_rate": round(1.0 - A / max(1, k * lc.T), 5) if lc.n_local == lc.E else None,
+        "layer_tflops": round((flops_router + flops_up + flops_dn) / (ms_per_step * 1e-3) / 1e12, 2),
+        "ffn_up_tflops": round(tflops_up, 2), "ffn_down_tflops": round(tflops_dn, 2),
+        "ffn_frac_of_mfma_peak": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
+                                       / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "gate_gbs": round(bytes_gate / (st["gate"] * 1e-3) / 1e9, 1),
+        "slice_gbs": round(bytes_slice / (st["slice"] * 1e-3) / 1e9, 1),
+        "combine_gbs": round(bytes_combine / (st["combine"] * 1e-3) / 1e9, 1),
+        "slice_frac_of_hbm_peak": round(bytes_slice / (st["slice"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "combine_frac_of_hbm_peak": round(bytes_combine / (st["combine"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+    }
+    log("[bench] " + json.dumps(detail))
+
+    result = {
+        "metric": "MoE-layer fwd tokens/s at d=2048,E=8,top-1 bf16; % MFMA peak (GEMM), % HBM (slice)",
+        "value": lc.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": lc.in_dtype, "data": "synthetic",
+        "config": {"workload": f"{lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
+                               f"top_k={lc.top_k} capacity_factor={lc.capacity_factor} "
+                               f"{lc.in_dtype} in / {lc.out_dtype} out, seed {lc.seed}"},
+        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<GELU> (ffn_up)",
+                     "achieved": tflops_up, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops_up / PEAK_BF16_TFLOPS, "traffic": None},
+        "detail": detail,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a token sample")
+        result["cpu_baseline"] = cpu_baseline(lc, inp, min(args.cpu_sample, lc.T))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,178 @@
+/* ppmoe.h -- C ABI of libppmoe.so: the MoE-layer forward of Pipeline MoE (PPMoE) on one device's
+ * share of a tensor-parallel group, as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * The path is Algorithm 1 of the paper without its closing all-reduce:
+ *   gate (linear map, softmax, top-k)  ->  tensor-index-slicing dispatch  ->  local expert FFNs
+ *   ->  gate-weighted combine into the zero-initialised partial output [T, d].
+ *
+ * Conventions that hold for every function below
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, row-major and
+ *     contiguous.  Only `const moe_config*` and `stage_events` arrays are HOST pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued
+ *     asynchronously; nothing here synchronises, allocates or frees device memory.  Results are
+ *     valid once the caller has synchronised the stream.
+ *   - Return value: MOE_OK (0) or a negative moe_status.  Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued.
+ *   - Weights are stored [out, in] (the contraction index is contiguous):
+ *     Wg[E, d], W1[N, F, d] (the paper's A_i transposed), W2[N, d, F] (B_i transposed).
+ *   - in_dtype is the type of x, Wg, W1, W2, x_sliced, H, y_sliced; out_dtype the type of `out`.
+ *     Supported pairs: (F32, F32), (BF16, BF16), (BF16, F32).  Logits, softmax and gate weights are
+ *     always float32 (the paper keeps the gating module in float32, Section 4.1); GEMMs accumulate
+ *     in float32.
+ *   - Shapes: T >= 0 tokens, d and F multiples of 8, 1 <= top_k <= E <= 256, top_k <= 8,
+ *     0 <= local_begin, local_begin + local_count <= E, local_count >= 1, k*T < 2^31.
+ *   - Inputs are assumed finite.  With NaN logits the pick order is unspecified.
+ */
+#ifndef PPMOE_H
+#define PPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_NULL = -1,      /* a required pointer is NULL                              */
+  MOE_ERR_SHAPE = -2,     /* a size violates the limits listed above                 */
+  MOE_ERR_DTYPE = -3,     /* unsupported (in_dtype, out_dtype) pair                  */
+  MOE_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned                 */
+  MOE_ERR_WORKSPACE = -5, /* workspace_bytes smaller than moe_workspace_bytes(cfg)   */
+  MOE_ERR_HIP = -6        /* a HIP runtime call (launch, event record) failed        */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/* Problem statement of one MoE layer on one device (Sections 3.3.1-3.3.3):
+ * T = b*s token embeddings of size d = h, E experts in the tensor-parallel group of which this
+ * device holds the contiguous block [local_begin, local_begin + local_count), a top_k gating
+ * schedule, and an optional capacity limit (PPMoE itself runs without one, Section 4.1). */
+typedef struct {
+  int32_t T, d, F;          /* tokens, hidden size, FFN inner size                             */
+  int32_t E, top_k;         /* experts in the group, picks per token                           */
+  int32_t local_begin, local_count;
+  float capacity_factor;    /* <= 0: no limit; else every expert keeps the first
+                               C = ceil(capacity_factor * top_k * T / E) assignments of its
+                               queue (ascending t*top_k + j) and drops the rest              */
+  int32_t renorm_topk;      /* 1: gate weights are divided by their sum over the k picks       */
+  int32_t in_dtype;         /* moe_dtype                                                       */
+  int32_t out_dtype;        /* moe_dtype                                                       */
+} moe_config;
+
+/* Stages of the fused call, in launch order; moe_layer_forward records stage_events[i] before
+ * stage i and stage_events[MOE_NUM_STAGES] after the last one. */
+enum {
+  MOE_STAGE_GATE = 0,     /* router GEMM + softmax + top-k                         */
+  MOE_STAGE_PERMUTE = 1,  /* histogram, scan, stable positions                     */
+  MOE_STAGE_SLICE = 2,    /* row gather into x_sliced                              */
+  MOE_STAGE_FFN_UP = 3,   /* grouped GEMM  H = GeLU(x_sliced W1^T)                 */
+  MOE_STAGE_FFN_DOWN = 4, /* grouped GEMM  y_sliced = H W2^T                       */
+  MOE_STAGE_COMBINE = 5,  /* gate-weighted gather into out                         */
+  MOE_NUM_STAGES = 6
+};
+
+/* Host-only helpers ------------------------------------------------------------------------- */
+
+/* Text for a moe_status value (static storage, never NULL). */
+const char* moe_status_string(int status);
+
+/* Per-expert queue limit C for this configuration, or -1 when capacity_factor <= 0.
+ * Computed in double precision exactly as ceil((double)cf * top_k * T / E). */
+int64_t moe_capacity(const moe_config* cfg);
+
+/* Upper bound on packed rows: top_k*T without a capacity limit, else
+ * min(top_k*T, local_count*C).  Buffers indexed by packed row (perm, x_sliced, H, y_sliced) must
+ * hold this many rows. */
+int64_t moe_max_rows(const moe_config* cfg);
+
+/* Bytes of scratch the largest consumer (moe_layer_forward) needs.  0 on an invalid config. */
+size_t moe_workspace_bytes(const moe_config* cfg);
+
+/* Bytes of scratch moe_slice_dispatch needs (per-segment counters of the permutation); never more
+ * than moe_workspace_bytes(cfg).  0 on an invalid config. */
+size_t moe_dispatch_workspace_bytes(const moe_config* cfg);
+
+/* Stage entry points ------------------------------------------------------------------------ */
+
+/* Gating module (Section 3.3.3; Algorithm 1: wg, softmax, gate_function).
+ *   logits[t, e] = sum_i x[t, i] * Wg[e, i] + bias[e]           (float32 accumulation)
+ *   p = softmax over all E experts; the top_k largest logits are picked, equal logits going to the
+ *   lower expert index; expert_idx[t, :] lists the picks in descending-logit order and
+ *   gate_w[t, j] = p[t, expert_idx[t, j]], divided by its sum over j when cfg->renorm_topk.
+ * x [T, d] in_dtype; Wg [E, d] in_dtype; bias [E] float32 or NULL.
+ * logits_in [T, E] float32 or NULL: when given, x/Wg/bias are ignored (may be NULL) and these
+ * logits are used verbatim.  logits_out [T, E] float32 or NULL receives the logits used.
+ * expert_idx [T, top_k] int32 and gate_w [T, top_k] float32 are written in full. */
+int moe_gate(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+             const float* logits_in, float* logits_out, int32_t* expert_idx, float* gate_w,
+             void* stream);
+
+/* Tensor-index-slicing dispatch (Sections 3.3.1 and 3.3.3, the index selection that replaces the
+ * first all-to-all; Algorithm 1: sliced_inputs).  Assignment id a = t*top_k + j.  The queue of an
+ * expert is every assignment that picked it, in ascending a; with a capacity limit only the first
+ * C are kept.  The kept queues of the local experts are packed end to end in ascending expert
+ * order (the paper's worked example: order 2,3,1,2,0,3,2,0 gives [4,7] [2] [0,3,6] [1,5]).
+ *   counts [local_count]        kept queue lengths
+ *   offsets [local_count + 1]   exclusive prefix sum of counts
+ *   perm [moe_max_rows]         perm[r] = assignment id in packed row r, r < offsets[local_count]
+ *   inv_perm [T, top_k]         packed row of (t, j), or -1 when dropped or not local
+ *   x_sliced [moe_max_rows, d]  x_sliced[r, :] = x[perm[r] / top_k, :]; NULL skips the row copy
+ * Rows at or beyond offsets[local_count] of perm and x_sliced are left untouched.
+ * workspace: at least moe_dispatch_workspace_bytes(cfg) bytes of device scratch. */
+int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expert_idx,
+                       int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                       void* x_sliced, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Local experts (Section 3.3.2: the N experts of a device; FFN of Section 3.1.3, GeLU(X A) B with
+ * the tanh form of GeLU and no bias), evaluated as two grouped GEMMs over the packed rows:
+ *   H[r, :]        = GeLU(x_sliced[r, :] . W1[i]^T)   for offsets[i] <= r < offsets[i+1]
+ *   y_sliced[r, :] = H[r, :] . W2[i]^T
+ * x_sliced [rows, d], H [rows, F] (scratch the caller provides), y_sliced [rows, d], all in_dtype,
+ * rows = moe_max_rows(cfg); offsets is the device array moe_slice_dispatch wrote (never read on
+ * the host).  Rows at or beyond offsets[local_count] are not written.
+ * moe_expert_ffn_up / _down run one of the two GEMMs each; moe_expert_ffn runs both. */
+int moe_expert_ffn_up(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                      const void* W1, void* H, void* stream);
+int moe_expert_ffn_down(const moe_config* cfg, const void* H, const int32_t* offsets,
+                        const void* W2, void* y_sliced, void* stream);
+int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                   const void* W1, const void* W2, void* H, void* y_sliced, void* stream);
+
+/* Combine (Sections 3.3.1/3.3.3, the index assignment that replaces the second all-to-all;
+ * Algorithm 1: zeros_like + placement):
+ *   out[t, :] = sum over j ascending with inv_perm[t, j] >= 0 of gate_w[t, j] * y_sliced[inv_perm[t, j], :]
+ * accumulated in float32 and rounded once to out_dtype; rows with no kept local pick are +0.
+ * Every row of out [T, d] is written exactly once (no atomics, no separate zero fill). */
+int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_perm,
+                const float* gate_w, void* out, void* stream);
+
+/* The whole layer (Algorithm 1 up to, not including, reduce_from_tensor_parallel_region): the six
+ * stages above on one stream with no host round trip.  Intermediates live in `workspace`
+ * (>= moe_workspace_bytes(cfg)); `out` [T, d] out_dtype is the partial sum this device would
+ * contribute to the all-reduce.
+ * stage_events: NULL, or a HOST array of MOE_NUM_STAGES + 1 hipEvent_t handles (as void*) that are
+ * recorded on `stream` around the stages, for timing. */
+int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                      const void* W1, const void* W2, void* out, void* workspace,
+                      size_t workspace_bytes, void* const* stage_events, void* stream);
+
+/* Where moe_layer_forward keeps its intermediates inside `workspace` (byte offsets), so a caller
+ * can inspect them after a run.  Any pointer may be NULL. */
+typedef struct {
+  size_t expert_idx, gate_w, counts, offsets, perm, inv_perm, x_sliced, H, y_sliced, scratch;
+} moe_workspace_layout;
+int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout);
+
+/* Timing helpers: thin wrappers over hipEvent so a caller without HIP headers can time stages.
+ * moe_event_elapsed_ms synchronises on `stop` before reading. */
+int moe_event_create(void** event);
+int moe_event_destroy(void* event);
+int moe_event_record(void* event, void* stream);
+int moe_event_elapsed_ms(void* start, void* stop, float* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPMOE_H */

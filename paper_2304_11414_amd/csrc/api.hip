@@ -1,0 +1,299 @@
+// Host side of libppmoe.so: argument validation, workspace layout and the launch sequence of
+// Algorithm 1 (without its closing all-reduce).  Nothing here synchronises or allocates.
+
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+using namespace ppmoe;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline size_t elem_bytes(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+int check_config(const moe_config* c) {
+  if (c == nullptr) return MOE_ERR_NULL;
+  if (c->T < 0 || c->d <= 0 || c->F <= 0 || (c->d & 7) || (c->F & 7)) return MOE_ERR_SHAPE;
+  if (c->E < 1 || c->E > kMaxExperts) return MOE_ERR_SHAPE;
+  if (c->top_k < 1 || c->top_k > c->E || c->top_k > kMaxTopK) return MOE_ERR_SHAPE;
+  if (c->local_begin < 0 || c->local_count < 1 || c->local_begin + c->local_count > c->E)
+    return MOE_ERR_SHAPE;
+  if (static_cast<int64_t>(c->T) * c->top_k >= (1ll << 31)) return MOE_ERR_SHAPE;
+  const bool ok = (c->in_dtype == MOE_F32 && c->out_dtype == MOE_F32) ||
+                  (c->in_dtype == MOE_BF16 && (c->out_dtype == MOE_BF16 || c->out_dtype == MOE_F32));
+  if (!ok) return MOE_ERR_DTYPE;
+  if (!(c->capacity_factor == c->capacity_factor)) return MOE_ERR_SHAPE;  // NaN
+  return MOE_OK;
+}
+
+int64_t capacity_of(const moe_config& c) {
+  if (!(c.capacity_factor > 0.f)) return -1;
+  double v = std::ceil(static_cast<double>(c.capacity_factor) * c.top_k * c.T / c.E);
+  if (v > 2147483647.0) v = 2147483647.0;
+  return static_cast<int64_t>(v);
+}
+
+int64_t max_rows_of(const moe_config& c) {
+  const int64_t all = static_cast<int64_t>(c.T) * c.top_k;
+  const int64_t cap = capacity_of(c);
+  int64_t per_expert = c.T;  // an expert is picked at most once per token (Section 4.1: at most b*s)
+  if (cap >= 0 && cap < per_expert) per_expert = cap;
+  const int64_t by_expert = per_expert * c.local_count;
+  return by_expert < all ? by_expert : all;
+}
+
+size_t dispatch_scratch_bytes(const moe_config& c) {
+  int64_t segs = n_segments(c);
+  if (segs < 1) segs = 1;
+  return static_cast<size_t>(2 * segs + 1) * c.local_count * sizeof(int32_t);
+}
+
+void layout_of(const moe_config& c, moe_workspace_layout* L, size_t* total) {
+  const size_t tk = static_cast<size_t>(c.T) * c.top_k;
+  const size_t rows = static_cast<size_t>(max_rows_of(c));
+  const size_t eb = elem_bytes(c.in_dtype);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes);
+    return at;
+  };
+  L->scratch = take(dispatch_scratch_bytes(c));  // first, so moe_slice_dispatch can use the base
+  L->expert_idx = take(tk * 4);
+  L->gate_w = take(tk * 4);
+  L->counts = take(static_cast<size_t>(c.local_count) * 4);
+  L->offsets = take(static_cast<size_t>(c.local_count + 1) * 4);
+  L->perm = take(rows * 4);
+  L->inv_perm = take(tk * 4);
+  L->x_sliced = take(rows * c.d * eb);
+  L->H = take(rows * c.F * eb);
+  L->y_sliced = take(rows * c.d * eb);
+  *total = off;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_NULL: return "a required pointer is NULL";
+    case MOE_ERR_SHAPE: return "a size is outside the supported range";
+    case MOE_ERR_DTYPE: return "unsupported (in_dtype, out_dtype) pair";
+    case MOE_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case MOE_ERR_WORKSPACE: return "workspace too small";
+    case MOE_ERR_HIP: return "a HIP runtime call failed";
+    default: return "unknown status";
+  }
+}
+
+int64_t moe_capacity(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return -1;
+  return capacity_of(*cfg);
+}
+
+int64_t moe_max_rows(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return 0;
+  return max_rows_of(*cfg);
+}
+
+size_t moe_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return 0;
+  moe_workspace_layout L;
+  size_t total = 0;
+  layout_of(*cfg, &L, &total);
+  return total;
+}
+
+size_t moe_dispatch_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return 0;
+  return dispatch_scratch_bytes(*cfg);
+}
+
+int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (layout == nullptr) return MOE_ERR_NULL;
+  size_t total = 0;
+  layout_of(*cfg, layout, &total);
+  return MOE_OK;
+}
+
+int moe_gate(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+             const float* logits_in, float* logits_out, int32_t* expert_idx, float* gate_w,
+             void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (expert_idx == nullptr || gate_w == nullptr) return MOE_ERR_NULL;
+  if (logits_in == nullptr && (x == nullptr || Wg == nullptr)) return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(Wg) || misaligned(bias) || misaligned(logits_in) ||
+      misaligned(logits_out) || misaligned(expert_idx) || misaligned(gate_w))
+    return MOE_ERR_ALIGN;
+  return hip_status(launch_gate(*cfg, x, Wg, bias, logits_in, logits_out, expert_idx, gate_w,
+                                static_cast<hipStream_t>(stream)));
+}
+
+int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expert_idx,
+                       int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                       void* x_sliced, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (counts == nullptr || offsets == nullptr || workspace == nullptr) return MOE_ERR_NULL;
+  if (cfg->T > 0 && (expert_idx == nullptr || perm == nullptr || inv_perm == nullptr))
+    return MOE_ERR_NULL;  // with T == 0 the per-token arrays are empty and may be NULL
+  if (cfg->T > 0 && x_sliced != nullptr && x == nullptr) return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(expert_idx) || misaligned(counts) || misaligned(offsets) ||
+      misaligned(perm) || misaligned(inv_perm) || misaligned(x_sliced) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  if (workspace_bytes < dispatch_scratch_bytes(*cfg)) return MOE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_permute(*cfg, capacity_of(*cfg), expert_idx, counts, offsets, perm, inv_perm,
+                                static_cast<int32_t*>(workspace), s);
+  if (e != hipSuccess) return MOE_ERR_HIP;
+  if (x_sliced != nullptr)
+    e = launch_slice(*cfg, x, perm, offsets, x_sliced, max_rows_of(*cfg), s);
+  return hip_status(e);
+}
+
+int moe_expert_ffn_up(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                      const void* W1, void* H, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (x_sliced == nullptr || offsets == nullptr || W1 == nullptr || H == nullptr) return MOE_ERR_NULL;
+  if (misaligned(x_sliced) || misaligned(offsets) || misaligned(W1) || misaligned(H))
+    return MOE_ERR_ALIGN;
+  return hip_status(launch_grouped_gemm(cfg->in_dtype, true, x_sliced, W1, H, offsets,
+                                        cfg->local_count, max_rows_of(*cfg), cfg->F, cfg->d,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int moe_expert_ffn_down(const moe_config* cfg, const void* H, const int32_t* offsets,
+                        const void* W2, void* y_sliced, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (H == nullptr || offsets == nullptr || W2 == nullptr || y_sliced == nullptr) return MOE_ERR_NULL;
+  if (misaligned(H) || misaligned(offsets) || misaligned(W2) || misaligned(y_sliced))
+    return MOE_ERR_ALIGN;
+  return hip_status(launch_grouped_gemm(cfg->in_dtype, false, H, W2, y_sliced, offsets,
+                                        cfg->local_count, max_rows_of(*cfg), cfg->d, cfg->F,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                   const void* W1, const void* W2, void* H, void* y_sliced, void* stream) {
+  if (W2 == nullptr || y_sliced == nullptr) return MOE_ERR_NULL;
+  if (misaligned(W2) || misaligned(y_sliced)) return MOE_ERR_ALIGN;
+  int st = moe_expert_ffn_up(cfg, x_sliced, offsets, W1, H, stream);
+  if (st != MOE_OK) return st;
+  return moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, stream);
+}
+
+int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_perm,
+                const float* gate_w, void* out, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (y_sliced == nullptr || inv_perm == nullptr || gate_w == nullptr || out == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(y_sliced) || misaligned(inv_perm) || misaligned(gate_w) || misaligned(out))
+    return MOE_ERR_ALIGN;
+  return hip_status(launch_combine(*cfg, y_sliced, inv_perm, gate_w, out,
+                                   static_cast<hipStream_t>(stream)));
+}
+
+int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                      const void* W1, const void* W2, void* out, void* workspace,
+                      size_t workspace_bytes, void* const* stage_events, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (x == nullptr || Wg == nullptr || W1 == nullptr || W2 == nullptr || out == nullptr ||
+      workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(Wg) || misaligned(bias) || misaligned(W1) || misaligned(W2) ||
+      misaligned(out) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  moe_workspace_layout L;
+  size_t total = 0;
+  layout_of(*cfg, &L, &total);
+  if (workspace_bytes < total) return MOE_ERR_WORKSPACE;
+  if (stage_events != nullptr)
+    for (int i = 0; i <= MOE_NUM_STAGES; ++i)
+      if (stage_events[i] == nullptr) return MOE_ERR_NULL;
+
+  const moe_config& c = *cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int32_t* expert_idx = reinterpret_cast<int32_t*>(ws + L.expert_idx);
+  float* gate_w = reinterpret_cast<float*>(ws + L.gate_w);
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+  int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(ws + L.inv_perm);
+  void* x_sliced = ws + L.x_sliced;
+  void* H = ws + L.H;
+  void* y_sliced = ws + L.y_sliced;
+  const int64_t rows = max_rows_of(c);
+
+  auto mark = [&](int i) -> hipError_t {
+    if (stage_events == nullptr) return hipSuccess;
+    return hipEventRecord(static_cast<hipEvent_t>(stage_events[i]), s);
+  };
+  hipError_t e;
+#define PPMOE_TRY(expr)                  \
+  do {                                   \
+    e = (expr);                          \
+    if (e != hipSuccess) return MOE_ERR_HIP; \
+  } while (0)
+
+  PPMOE_TRY(mark(MOE_STAGE_GATE));
+  PPMOE_TRY(launch_gate(c, x, Wg, bias, nullptr, nullptr, expert_idx, gate_w, s));
+  PPMOE_TRY(mark(MOE_STAGE_PERMUTE));
+  PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm,
+                           reinterpret_cast<int32_t*>(ws + L.scratch), s));
+  PPMOE_TRY(mark(MOE_STAGE_SLICE));
+  PPMOE_TRY(launch_slice(c, x, perm, offsets, x_sliced, rows, s));
+  PPMOE_TRY(mark(MOE_STAGE_FFN_UP));
+  PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x_sliced, W1, H, offsets, c.local_count, rows, c.F,
+                                c.d, s));
+  PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
+  PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, y_sliced, offsets, c.local_count, rows,
+                                c.d, c.F, s));
+  PPMOE_TRY(mark(MOE_STAGE_COMBINE));
+  PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s));
+  PPMOE_TRY(mark(MOE_NUM_STAGES));
+#undef PPMOE_TRY
+  return MOE_OK;
+}
+
+int moe_event_create(void** event) {
+  if (event == nullptr) return MOE_ERR_NULL;
+  hipEvent_t ev;
+  if (hipEventCreate(&ev) != hipSuccess) return MOE_ERR_HIP;
+  *event = ev;
+  return MOE_OK;
+}
+
+int moe_event_destroy(void* event) {
+  if (event == nullptr) return MOE_ERR_NULL;
+  return hip_status(hipEventDestroy(static_cast<hipEvent_t>(event)));
+}
+
+int moe_event_record(void* event, void* stream) {
+  if (event == nullptr) return MOE_ERR_NULL;
+  return hip_status(hipEventRecord(static_cast<hipEvent_t>(event), static_cast<hipStream_t>(stream)));
+}
+
+int moe_event_elapsed_ms(void* start, void* stop, float* ms) {
+  if (start == nullptr || stop == nullptr || ms == nullptr) return MOE_ERR_NULL;
+  if (hipEventSynchronize(static_cast<hipEvent_t>(stop)) != hipSuccess) return MOE_ERR_HIP;
+  return hip_status(hipEventElapsedTime(ms, static_cast<hipEvent_t>(start),
+                                        static_cast<hipEvent_t>(stop)));
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal declarations shared by the kernels of libppmoe.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ppmoe.h"
+
+namespace ppmoe {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kMaxExperts = 256;   // E limit of the ABI
+constexpr int kMaxTopK = 8;
+constexpr int kSegment = 512;      // assignments ranked by one wavefront in the permutation
+
+typedef uint16_t bf16_t;           // raw bf16 bits in memory
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte piece
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+// Launchers (host).  Each returns the hipError_t of its last launch.
+hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
+                       const float* logits_in, float* logits_out, int32_t* expert_idx,
+                       float* gate_w, hipStream_t s);
+
+// seg_scratch: int32[(local_count) * n_segments * 2 + local_count] device scratch.
+hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* expert_idx,
+                          int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                          int32_t* seg_scratch, hipStream_t s);
+
+hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
+                        const int32_t* offsets, void* x_sliced, int64_t max_rows, hipStream_t s);
+
+hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
+                          const float* gate_w, void* out, hipStream_t s);
+
+// C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
+hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
+                               const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
+                               hipStream_t s);
+
+inline int64_t n_segments(const moe_config& c) {
+  int64_t a = static_cast<int64_t>(c.T) * c.top_k;
+  return (a + kSegment - 1) / kSegment;
+}
+
+}  // namespace ppmoe

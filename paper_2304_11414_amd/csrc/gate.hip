@@ -1,0 +1,234 @@
+// Gating module: router GEMM + softmax + top-k in one pass over the token matrix.
+// Section 3.3.3 of the paper (linear mapping, softmax score function, gating schedule);
+// Algorithm 1: logits = wg(hidden_states); scores = softmax(logits); gate_function(scores).
+//
+// The router GEMM is skinny (N = E <= 256) and reads x exactly once, so it is HBM-bound; it runs on
+// the 16x16x32 bf16 MFMA so that the arithmetic never becomes the limit at E = 64.  Softmax and the
+// top-k selection are float32 (the paper keeps the gating module in float32, Section 4.1).
+
+#include "common.h"
+
+namespace ppmoe {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+
+// One token: softmax over all E logits, then k picks in descending (logit, then ascending index)
+// order.  Picks are found without a "taken" mask: the next pick is the largest element that comes
+// strictly after the previous pick in that order.
+__device__ __forceinline__ void softmax_topk_row(const float* lg, int E, int k, int renorm,
+                                                 int32_t* idx_out, float* w_out) {
+  float m = lg[0];
+  for (int e = 1; e < E; ++e) m = fmaxf(m, lg[e]);
+  float sum = 0.f;
+  for (int e = 0; e < E; ++e) sum += expf(lg[e] - m);
+  float pv = __builtin_inff();
+  int pe = -1;
+  float wsum = 0.f;
+  for (int j = 0; j < k; ++j) {
+    int best = -1;
+    float bv = 0.f;
+    for (int e = 0; e < E; ++e) {
+      float v = lg[e];
+      bool after_prev = (v < pv) || (v == pv && e > pe);
+      if (after_prev && (best < 0 || v > bv)) {
+        best = e;
+        bv = v;
+      }
+    }
+    float w = expf(bv - m) / sum;
+    idx_out[j] = best;
+    w_out[j] = w;
+    wsum += w;
+    pv = bv;
+    pe = best;
+  }
+  if (renorm) {
+    for (int j = 0; j < k; ++j) w_out[j] = w_out[j] / wsum;
+  }
+}
+
+// bf16 router: a block owns 16*MT tokens; its 4 wavefronts split d between them (span-interleaved)
+// and their partial logits are added in wavefront order through LDS, so the float32 sum order is
+// fixed.  MFMA operands come straight from global memory: lane (r = lane%16, g = lane/16) holds 8
+// consecutive k of row r, which is exactly a 16-byte load; four such loads cover 64 contiguous
+// bytes of each of the 16 rows.
+template <int NT, int MT>
+__global__ __launch_bounds__(256) void gate_bf16_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg, const float* __restrict__ bias,
+    float* __restrict__ logits_out, int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
+    int T, int d, int E, int k, int renorm) {
+  constexpr int kTok = 16 * MT;
+  constexpr int kLd = NT * 16 + 1;
+  __shared__ float red[kTok * kLd];
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const int t0 = blockIdx.x * kTok;
+  const int nchunk = d >> 3;  // 16-byte chunks per row
+
+  const u32x4* xrow[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int t = min(t0 + mt * 16 + r, T - 1);
+    xrow[mt] = reinterpret_cast<const u32x4*>(x + static_cast<size_t>(t) * d);
+  }
+  const u32x4* wrow[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int e = min(nt * 16 + r, E - 1);
+    wrow[nt] = reinterpret_cast<const u32x4*>(Wg + static_cast<size_t>(e) * d);
+  }
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  for (int c0 = wave * 16; c0 < nchunk; c0 += 64) {
+    u32x4 a[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int c = c0 + i * 4 + g;
+        a[mt][i] = c < nchunk ? __builtin_nontemporal_load(xrow[mt] + c) : zero;
+      }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int c = c0 + i * 4 + g;
+        u32x4 b = c < nchunk ? wrow[nt][c] : zero;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8, a[mt][i]), __builtin_bit_cast(bf16x8, b), acc[mt][nt], 0, 0, 0);
+      }
+    }
+  }
+
+  // D layout of the 16x16 MFMA: lane holds column (lane % 16), rows (lane / 16) * 4 + i.
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float* p = &red[(mt * 16 + g * 4 + i) * kLd + nt * 16 + r];
+            *p = (w == 0) ? acc[mt][nt][i] : (*p + acc[mt][nt][i]);
+          }
+    }
+    __syncthreads();
+  }
+
+  if (threadIdx.x < kTok) {
+    int t = t0 + threadIdx.x;
+    if (t < T) {
+      float* lg = &red[threadIdx.x * kLd];
+      if (bias != nullptr)
+        for (int e = 0; e < E; ++e) lg[e] += bias[e];
+      if (logits_out != nullptr)
+        for (int e = 0; e < E; ++e) logits_out[static_cast<size_t>(t) * E + e] = lg[e];
+      softmax_topk_row(lg, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
+                       gate_w + static_cast<size_t>(t) * k);
+    }
+  }
+}
+
+// float32 router (the small parity configuration): one wavefront per token, experts four at a time,
+// fixed butterfly reduction order.
+__global__ __launch_bounds__(256) void gate_f32_kernel(
+    const float* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bias,
+    float* __restrict__ logits_out, int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
+    int T, int d, int E, int k, int renorm) {
+  __shared__ float red[4][kMaxExperts];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;  // whole wavefront leaves; no block-wide barrier below
+  const float4* xr = reinterpret_cast<const float4*>(x + static_cast<size_t>(t) * d);
+  const int nq = d >> 2;
+  for (int e0 = 0; e0 < E; e0 += 4) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int q = lane; q < nq; q += 64) {
+      float4 xv = xr[q];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int e = min(e0 + j, E - 1);
+        float4 wv = reinterpret_cast<const float4*>(Wg + static_cast<size_t>(e) * d)[q];
+        acc[j] = fmaf(xv.x, wv.x, acc[j]);
+        acc[j] = fmaf(xv.y, wv.y, acc[j]);
+        acc[j] = fmaf(xv.z, wv.z, acc[j]);
+        acc[j] = fmaf(xv.w, wv.w, acc[j]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float v = acc[j];
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+      if (lane == 0 && e0 + j < E) red[wave][e0 + j] = v + (bias ? bias[e0 + j] : 0.f);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane == 0) {
+    float* lg = red[wave];
+    if (logits_out != nullptr)
+      for (int e = 0; e < E; ++e) logits_out[static_cast<size_t>(t) * E + e] = lg[e];
+    softmax_topk_row(lg, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
+                     gate_w + static_cast<size_t>(t) * k);
+  }
+}
+
+// Logits handed in by the caller: one thread per token.
+__global__ __launch_bounds__(256) void gate_from_logits_kernel(
+    const float* __restrict__ logits_in, float* __restrict__ logits_out,
+    int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, int T, int E, int k, int renorm) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float* lg = logits_in + static_cast<size_t>(t) * E;
+  if (logits_out != nullptr && logits_out != logits_in)
+    for (int e = 0; e < E; ++e) logits_out[static_cast<size_t>(t) * E + e] = lg[e];
+  softmax_topk_row(lg, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
+                   gate_w + static_cast<size_t>(t) * k);
+}
+
+template <int NT, int MT>
+static void launch_bf16(const moe_config& c, const void* x, const void* Wg, const float* bias,
+                        float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s) {
+  int blocks = (c.T + 16 * MT - 1) / (16 * MT);
+  gate_bf16_kernel<NT, MT><<<blocks, 256, 0, s>>>(
+      static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(Wg), bias, logits_out, expert_idx,
+      gate_w, c.T, c.d, c.E, c.top_k, c.renorm_topk);
+}
+
+hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
+                       const float* logits_in, float* logits_out, int32_t* expert_idx,
+                       float* gate_w, hipStream_t s) {
+  if (c.T == 0) return hipSuccess;
+  if (logits_in != nullptr) {
+    gate_from_logits_kernel<<<(c.T + 255) / 256, 256, 0, s>>>(logits_in, logits_out, expert_idx,
+                                                              gate_w, c.T, c.E, c.top_k,
+                                                              c.renorm_topk);
+  } else if (c.in_dtype == MOE_F32) {
+    gate_f32_kernel<<<(c.T + 3) / 4, 256, 0, s>>>(static_cast<const float*>(x),
+                                                  static_cast<const float*>(Wg), bias, logits_out,
+                                                  expert_idx, gate_w, c.T, c.d, c.E, c.top_k,
+                                                  c.renorm_topk);
+  } else if (c.E <= 16) {
+    launch_bf16<1, 1>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+  } else if (c.E <= 32) {
+    launch_bf16<2, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+  } else if (c.E <= 64) {
+    launch_bf16<4, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+  } else if (c.E <= 128) {
+    launch_bf16<8, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+  } else {
+    launch_bf16<16, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ppmoe

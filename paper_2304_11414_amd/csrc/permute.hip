@@ -1,0 +1,187 @@
+// Dispatching order -> per-expert index lists (the "indices" of Algorithm 1; worked example of
+// Section 3.3.3: order 2,3,1,2,0,3,2,0 gives [4,7] [2] [0,3,6] [1,5]).
+//
+// The position of assignment a = t*k + j in its expert's queue is the number of earlier assignments
+// to the same expert.  It is computed without order-dependent atomics, so the permutation is
+// identical on every run and on every rank of a tensor-parallel group:
+//   1. every wavefront owns a segment of kSegment consecutive assignments and counts, per local
+//      expert, how many of them it holds (ballot + popcount, counts kept in registers);
+//   2. one wavefront per expert turns the per-segment counts into exclusive prefix sums;
+//   3. every wavefront walks its segment again, 64 assignments at a time: rank inside the step by
+//      ballot/popcount, plus the running count carried in registers, plus the segment's prefix.
+// counts/offsets (capacity-clamped, exclusive scan over the local experts) are rebuilt by every
+// wavefront of step 3 from the expert totals, which costs a few shuffles, and written by the first.
+
+#include "common.h"
+
+namespace ppmoe {
+
+constexpr int kRegs = kMaxExperts / kWave;  // lane i holds experts i, i+64, i+128, i+192
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// For a uniform expert id e: value of run[e / 64] held by lane e % 64.
+__device__ __forceinline__ int read_slot(const int (&run)[kRegs], int e) {
+  int v = 0;
+#pragma unroll
+  for (int c = 0; c < kRegs; ++c)
+    if ((e >> 6) == c) v = __shfl(run[c], e & 63, 64);
+  return v;
+}
+
+__device__ __forceinline__ void add_slot(int (&run)[kRegs], int e, int amount) {
+#pragma unroll
+  for (int c = 0; c < kRegs; ++c)
+    if ((e >> 6) == c && lane_id() == (e & 63)) run[c] += amount;
+}
+
+// Step 1.  seg_count[i * n_seg + seg] = number of assignments of segment seg that picked local
+// expert i.
+__global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __restrict__ expert_idx,
+                                                            int32_t* __restrict__ seg_count,
+                                                            int64_t n_assign, int n_seg,
+                                                            int local_begin, int n_local) {
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= n_seg) return;
+  const int lane = lane_id();
+  int run[kRegs] = {0, 0, 0, 0};
+  const int64_t base = static_cast<int64_t>(seg) * kSegment;
+  for (int step = 0; step < kSegment / kWave; ++step) {
+    int64_t a = base + step * kWave + lane;
+    int e = -1;
+    if (a < n_assign) {
+      unsigned le = static_cast<unsigned>(expert_idx[a] - local_begin);
+      if (le < static_cast<unsigned>(n_local)) e = static_cast<int>(le);
+    }
+    unsigned long long todo = __ballot(e >= 0);
+    while (todo) {
+      int leader = __ffsll(static_cast<long long>(todo)) - 1;
+      int e0 = __shfl(e, leader, 64);
+      unsigned long long same = __ballot(e == e0);
+      add_slot(run, e0, __popcll(same));
+      todo &= ~same;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kRegs; ++c) {
+    int i = c * kWave + lane;
+    if (i < n_local) seg_count[static_cast<int64_t>(i) * n_seg + seg] = run[c];
+  }
+}
+
+// Step 2.  One wavefront per local expert: seg_base = exclusive scan of seg_count over segments,
+// totals[i] = queue length of expert i before any capacity clamp.
+__global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
+                                                          int32_t* __restrict__ seg_base,
+                                                          int32_t* __restrict__ totals, int n_seg) {
+  const int i = blockIdx.x;
+  const int lane = lane_id();
+  const int32_t* in = seg_count + static_cast<int64_t>(i) * n_seg;
+  int32_t* out = seg_base + static_cast<int64_t>(i) * n_seg;
+  int carry = 0;
+  for (int s0 = 0; s0 < n_seg; s0 += kWave) {
+    int s = s0 + lane;
+    int v = s < n_seg ? in[s] : 0;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      int up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    if (s < n_seg) out[s] = carry + incl - v;
+    carry += __shfl(incl, kWave - 1, 64);
+  }
+  if (lane == 0) totals[i] = carry;
+}
+
+// Step 3.
+__global__ __launch_bounds__(256) void rank_kernel(
+    const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ seg_base,
+    const int32_t* __restrict__ totals, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int64_t n_assign, int n_seg,
+    int local_begin, int n_local, int cap /* INT_MAX when unlimited */) {
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= n_seg) return;
+  const int lane = lane_id();
+
+  // Kept queue lengths and their exclusive scan over the local experts (ascending expert id).
+  int kept[kRegs], off[kRegs], run[kRegs];
+  int carry = 0;
+#pragma unroll
+  for (int c = 0; c < kRegs; ++c) {
+    int i = c * kWave + lane;
+    kept[c] = i < n_local ? min(totals[i], cap) : 0;
+    int incl = kept[c];
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      int up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    off[c] = carry + incl - kept[c];
+    carry += __shfl(incl, kWave - 1, 64);
+    run[c] = i < n_local ? seg_base[static_cast<int64_t>(i) * n_seg + seg] : 0;
+    if (seg == 0 && i < n_local) {
+      counts[i] = kept[c];
+      offsets[i] = off[c];
+    }
+  }
+  if (seg == 0 && lane == 0) offsets[n_local] = carry;
+
+  const int64_t base = static_cast<int64_t>(seg) * kSegment;
+  for (int step = 0; step < kSegment / kWave; ++step) {
+    int64_t a = base + step * kWave + lane;
+    int e = -1;
+    if (a < n_assign) {
+      unsigned le = static_cast<unsigned>(expert_idx[a] - local_begin);
+      if (le < static_cast<unsigned>(n_local)) e = static_cast<int>(le);
+    }
+    int row = -1;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    unsigned long long todo = __ballot(e >= 0);
+    while (todo) {
+      int leader = __ffsll(static_cast<long long>(todo)) - 1;
+      int e0 = __shfl(e, leader, 64);
+      unsigned long long same = __ballot(e == e0);
+      int pos0 = read_slot(run, e0);   // queue position of the first of this group
+      int off0 = read_slot(off, e0);
+      if (e == e0) {
+        int pos = pos0 + __popcll(same & below);
+        if (pos < cap) row = off0 + pos;
+      }
+      add_slot(run, e0, __popcll(same));
+      todo &= ~same;
+    }
+    if (a < n_assign) {
+      inv_perm[a] = row;
+      if (row >= 0) perm[row] = static_cast<int32_t>(a);
+    }
+  }
+}
+
+hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* expert_idx,
+                          int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                          int32_t* seg_scratch, hipStream_t s) {
+  const int64_t n_assign = static_cast<int64_t>(c.T) * c.top_k;
+  const int n_seg = static_cast<int>(n_segments(c));
+  const int N = c.local_count;
+  int32_t* seg_count = seg_scratch;
+  int32_t* seg_base = seg_scratch + static_cast<int64_t>(N) * n_seg;
+  int32_t* totals = seg_base + static_cast<int64_t>(N) * n_seg;
+  const int cap_i = (cap < 0 || cap > 0x7fffffff) ? 0x7fffffff : static_cast<int>(cap);
+  const int blocks = n_seg > 0 ? (n_seg + 3) / 4 : 0;
+  if (blocks > 0)
+    segment_count_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_count, n_assign, n_seg,
+                                                c.local_begin, N);
+  segment_scan_kernel<<<N, 64, 0, s>>>(seg_count, seg_base, totals, n_seg);
+  if (blocks > 0) {
+    rank_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_base, totals, counts, offsets, perm,
+                                       inv_perm, n_assign, n_seg, c.local_begin, N, cap_i);
+  } else {
+    // T == 0: counts and offsets are still defined (all zero); one wavefront writes them.
+    rank_kernel<<<1, 64, 0, s>>>(expert_idx, seg_base, totals, counts, offsets, perm, inv_perm, 0, 1,
+                                 c.local_begin, N, cap_i);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ppmoe

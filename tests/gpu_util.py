@@ -1,0 +1,148 @@
+"""Helpers for the GPU parity tests: moving seeded NumPy inputs to the device, running the C-ABI
+stages, and the error measures the tolerances are written in."""
+
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2304_11414_amd import binding as B
+
+
+def torch_dtype(name):
+    import torch
+    return torch.bfloat16 if name == "bf16" else torch.float32
+
+
+def to_dev(a, dtype_name=None):
+    """NumPy array -> cuda tensor.  float arrays that hold bf16-representable values convert exactly."""
+    import torch
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    if dtype_name is not None:
+        t = t.to(torch_dtype(dtype_name))
+    return t.contiguous()
+
+
+def to_np(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.detach().cpu().numpy()
+
+
+def max_rel_err(got, ref):
+    """max |got - ref| / max |ref| over the compared tensor (the measure the 2e-2 / 1e-5 bars use;
+    a purely elementwise relative error is undefined on the exactly-zero rows)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.max(np.abs(ref)) if ref.size else 0.0
+    if scale == 0.0:
+        return float(np.max(np.abs(got))) if got.size else 0.0
+    return float(np.max(np.abs(got - ref)) / scale)
+
+
+def assert_close(got, ref, tol, what=""):
+    """The max-relative-error bar, plus an elementwise bound |got-ref| <= tol*(rms(ref) + |ref|)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    err = max_rel_err(got, ref)
+    assert err <= tol, f"{what}: max rel err {err:.3e} > {tol:.1e}"
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    bad = np.abs(got - ref) > tol * (rms + np.abs(ref))
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements outside tol*(rms+|ref|), tol={tol:.1e}"
+
+
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+
+class DeviceLayer:
+    """Device copies of one layer's inputs plus the scratch the stage calls need."""
+
+    def __init__(self, lc, inp):
+        import torch
+        self.lc = lc
+        self.cfg = B.config_from(lc)
+        self.x = to_dev(inp.get("x"), lc.in_dtype)
+        self.Wg = to_dev(inp.get("Wg_t"), lc.in_dtype)
+        self.bias = to_dev(inp.get("bias"))
+        self.W1 = to_dev(inp.get("W1_t"), lc.in_dtype)
+        self.W2 = to_dev(inp.get("W2_t"), lc.in_dtype)
+        self.rows = B.moe_max_rows(self.cfg)
+        self.torch = torch
+
+    def empty(self, shape, dtype):
+        return self.torch.empty(shape, dtype=dtype, device="cuda")
+
+    def workspace(self, fill=None):
+        n = B.moe_workspace_bytes(self.cfg)
+        ws = self.empty((max(n, 16),), self.torch.uint8)
+        if fill is not None:
+            ws.fill_(fill)
+        return ws
+
+    def run_gate(self, logits_in=None, want_logits=True):
+        t, c = self.torch, self.cfg
+        idx = self.empty((c.T, c.top_k), t.int32)
+        w = self.empty((c.T, c.top_k), t.float32)
+        lo = self.empty((c.T, c.E), t.float32) if want_logits else None
+        li = to_dev(logits_in) if logits_in is not None else None
+        B.moe_gate(c, self.x, self.Wg, self.bias, li, lo, idx, w)
+        t.cuda.synchronize()
+        return (to_np(lo) if lo is not None else None), to_np(idx), to_np(w)
+
+    def run_dispatch(self, expert_idx, with_rows=True):
+        t, c = self.torch, self.cfg
+        idx = to_dev(np.asarray(expert_idx, dtype=np.int32))
+        counts = self.empty((c.local_count,), t.int32)
+        offsets = self.empty((c.local_count + 1,), t.int32)
+        perm = t.full((max(self.rows, 1),), -7, dtype=t.int32, device="cuda")
+        inv = self.empty((c.T, c.top_k), t.int32)
+        xs = self.empty((max(self.rows, 1), c.d), torch_dtype(self.lc.in_dtype)) if with_rows else None
+        ws = self.empty((max(B.moe_dispatch_workspace_bytes(c), 16),), t.uint8)
+        B.moe_slice_dispatch(c, self.x, idx, counts, offsets, perm, inv, xs, ws)
+        t.cuda.synchronize()
+        return (to_np(counts), to_np(offsets), to_np(perm), to_np(inv),
+                to_np(xs) if xs is not None else None)
+
+    def run_ffn(self, x_sliced, offsets):
+        t, c = self.torch, self.cfg
+        et = torch_dtype(self.lc.in_dtype)
+        xs = self.empty((max(self.rows, 1), c.d), et)
+        xs.zero_()
+        n = x_sliced.shape[0]
+        if n:
+            xs[:n] = to_dev(np.asarray(x_sliced, dtype=np.float32), self.lc.in_dtype)
+        off = to_dev(np.asarray(offsets, dtype=np.int32))
+        H = self.empty((max(self.rows, 1), c.F), et)
+        y = self.empty((max(self.rows, 1), c.d), et)
+        B.moe_expert_ffn(c, xs, off, self.W1, self.W2, H, y)
+        t.cuda.synchronize()
+        return to_np(H[:n]), to_np(y[:n])
+
+    def run_combine(self, y_sliced, inv_perm, gate_w):
+        t, c = self.torch, self.cfg
+        y = self.empty((max(self.rows, 1), c.d), torch_dtype(self.lc.in_dtype))
+        n = y_sliced.shape[0]
+        if n:
+            y[:n] = to_dev(np.asarray(y_sliced, dtype=np.float32), self.lc.in_dtype)
+        inv = to_dev(np.asarray(inv_perm, dtype=np.int32))
+        w = to_dev(np.asarray(gate_w, dtype=np.float32))
+        out = self.empty((c.T, c.d), torch_dtype(self.lc.out_dtype))
+        out.fill_(7.0)
+        B.moe_combine(c, y, inv, w, out)
+        t.cuda.synchronize()
+        return to_np(out)
+
+    def run_layer(self, ws_fill=0xAB):
+        t, c = self.torch, self.cfg
+        ws = self.workspace(fill=ws_fill)
+        out = self.empty((c.T, c.d), torch_dtype(self.lc.out_dtype))
+        out.fill_(7.0)
+        B.moe_layer_forward(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, ws)
+        t.cuda.synchronize()
+        return out, B.workspace_views(c, ws)
