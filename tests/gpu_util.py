@@ -43,7 +43,8 @@ def max_rel_err(got, ref):
 
 
 def assert_close(got, ref, tol, what=""):
-    """The max-relative-error bar, plus an elementwise bound |got-ref| <= tol*(rms(ref) + |ref|)."""
+    """The max-relative-error bar, plus an elementwise bound |got-ref| <= tol*(rms(ref) + |ref|),
+    the rms taken over the non-zero elements of ref (exact-zero rows would dilute it)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
@@ -52,7 +53,8 @@ def assert_close(got, ref, tol, what=""):
     assert np.all(np.isfinite(got)), f"{what}: non-finite values"
     err = max_rel_err(got, ref)
     assert err <= tol, f"{what}: max rel err {err:.3e} > {tol:.1e}"
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    nz = ref != 0.0
+    rms = float(np.sqrt(np.mean(ref[nz] ** 2))) if nz.any() else 0.0
     bad = np.abs(got - ref) > tol * (rms + np.abs(ref))
     assert not bad.any(), f"{what}: {int(bad.sum())} elements outside tol*(rms+|ref|), tol={tol:.1e}"
 
