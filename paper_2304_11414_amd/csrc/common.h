@@ -29,8 +29,13 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return static_cast<bf16_t>(u >> 16);
 }
 
+// Two floats -> two bf16 in one 32-bit word (lo in bits 0..15), round to nearest even: the
+// hardware's packed conversion (v_cvt_pk_bf16_f32).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Launchers (host).  Each returns the hipError_t of its last launch.
@@ -53,6 +58,11 @@ hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                hipStream_t s);
+
+// bf16 fast path of the above (K a multiple of 64).
+hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
+                                    const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
+                                    int K, hipStream_t s);
 
 inline int64_t n_segments(const moe_config& c) {
   int64_t a = static_cast<int64_t>(c.T) * c.top_k;

@@ -93,7 +93,7 @@ constexpr int kTileBytes = kBM * kBK * 2;  // one operand tile in LDS: 32 KiB
 
 // Byte offset of 16-byte piece `ch` (0..7) of row `row` inside a tile: rows are 128 bytes, pieces are
 // XOR-swizzled with the row number.
-__device__ __forceinline__ int lds_piece(int row, int ch) { return row * 128 + ((ch ^ (row & 7)) << 4); }
+__device__ __forceinline__ int lds_piece(int row, int ch) { return row * 128 + ((ch ^ ((row >> 1) & 7)) << 4); }
 
 template <bool GELU>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
   int wgt_base = kTileBytes + (lds_piece(wn * 64 + frow, 0) & ~127);
   int piece[4];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) piece[ks] = ((2 * ks + half) ^ (frow & 7)) << 4;
+  for (int ks = 0; ks < 4; ++ks) piece[ks] = ((2 * ks + half) ^ ((frow >> 1) & 7)) << 4;
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -306,6 +306,10 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                hipStream_t s) {
   if (max_rows == 0) return hipSuccess;
+  if (in_dtype == MOE_BF16 && (K % 64) == 0) {
+    return launch_grouped_gemm_fast(gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
+                                    static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, s);
+  }
   if (in_dtype == MOE_BF16) {
     hipError_t e = ensure_lds_attr();
     if (e != hipSuccess) return e;
