@@ -41,8 +41,9 @@ constexpr int kLdsBytes = 2 * kBufBytes;       // 128 KiB
 
 __device__ __forceinline__ float gelu_tanh(float u) {
   // 0.5 u (1 + tanh(z)) = u / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3)
-  const float z2 = 1.5957691216057308f * u * fmaf(0.044715f * u, u, 1.0f);
-  return u / (1.0f + __expf(-z2));
+  // exp and the reciprocal are single hardware instructions (about 1 ulp each), ample for a bf16 result.
+  const float z2 = -2.302208198f * u * fmaf(0.044715f * u, u, 1.0f);   // -2 sqrt(2/pi) log2(e) (u + 0.044715 u^3)
+  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z2));
 }
 
 template <int OFF>
@@ -275,17 +276,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   // ---- epilogue ----------------------------------------------------------------------------------
   // D = W_frag (32 n) x Tok_frag^T (32 m): lane holds token m = lane & 31 and, in register v, output
   // column n = (v / 4) * 8 + (lane >> 5) * 4 + v % 4: four consecutive columns per group of 4.
+  // The 128 x 128 sub-tile of a wavefront goes through its own 32 KiB of LDS (rows of 256 bytes,
+  // 16-byte chunk c of row r at chunk c ^ (r & 15)) so that global stores are 16 bytes per lane and
+  // 256 contiguous bytes per row instead of 8-byte pieces scattered over 32 rows.
+  __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
+  const uint32_t epi = lds0 + wave * (128 * 256);
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
-    const int m = wm * 128 + mi * 32 + frow;
-    if (m >= tc.rows) continue;
-    bf16_t* crow = C + static_cast<size_t>(tc.row0 + m) * Nout + tc.col0;
+    const int r = mi * 32 + frow;
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = wn * 128 + ni * 32 + q * 8 + half * 4;
-        if (n >= cols) continue;
         float v0 = acc[mi][ni][q * 4 + 0], v1 = acc[mi][ni][q * 4 + 1];
         float v2 = acc[mi][ni][q * 4 + 2], v3 = acc[mi][ni][q * 4 + 3];
         if (GELU) {
@@ -294,12 +296,27 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
           v2 = gelu_tanh(v2);
           v3 = gelu_tanh(v3);
         }
-        uint2 p;
-        p.x = pack_bf16x2(v0, v1);
-        p.y = pack_bf16x2(v2, v3);
-        *reinterpret_cast<uint2*>(crow + n) = p;
+        const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
+        const uint32_t a = epi + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
+        const uint32_t lo = pack_bf16x2(v0, v1), hi = pack_bf16x2(v2, v3);
+        asm volatile("ds_write_b64 %0, %1" : : "v"(a), "v"(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32)) : "memory");
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // one row block at a time keeps the register footprint small
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  // Read back 16 bytes per lane: an instruction covers 4 rows x 256 bytes.
+  const int er = lane >> 4, ec = lane & 15;
+  const int ncol = cols - wn * 128;   // valid columns of this wavefront's half (may be <= 0)
+#pragma unroll 4
+  for (int i = 0; i < 32; ++i) {
+    const int r = i * 4 + er;
+    u32x4 v;
+    const uint32_t a = epi + r * 256 + ((ec ^ (r & 15)) << 4);
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    const int m = wm * 128 + r;
+    if (m < tc.rows && ec * 8 < ncol)
+      *reinterpret_cast<u32x4*>(C + static_cast<size_t>(tc.row0 + m) * Nout + tc.col0 + wn * 128 + ec * 8) = v;
   }
 }
 
