@@ -94,6 +94,10 @@ size_t moe_workspace_bytes(const moe_config* cfg);
  * than moe_workspace_bytes(cfg).  0 on an invalid config. */
 size_t moe_dispatch_workspace_bytes(const moe_config* cfg);
 
+/* Bytes of scratch the expert-FFN calls need (partial sums of output tiles whose k range is cut
+ * between compute units); never more than moe_workspace_bytes(cfg).  0 on an invalid config. */
+size_t moe_ffn_workspace_bytes(const moe_config* cfg);
+
 /* Stage entry points ------------------------------------------------------------------------ */
 
 /* Gating module (Section 3.3.3; Algorithm 1: wg, softmax, gate_function).
@@ -132,13 +136,18 @@ int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expe
  * x_sliced [rows, d], H [rows, F] (scratch the caller provides), y_sliced [rows, d], all in_dtype,
  * rows = moe_max_rows(cfg); offsets is the device array moe_slice_dispatch wrote (never read on
  * the host).  Rows at or beyond offsets[local_count] are not written.
+ * workspace: at least moe_ffn_workspace_bytes(cfg) bytes of device scratch; calls that share a
+ * workspace must be ordered on one stream.
  * moe_expert_ffn_up / _down run one of the two GEMMs each; moe_expert_ffn runs both. */
 int moe_expert_ffn_up(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
-                      const void* W1, void* H, void* stream);
+                      const void* W1, void* H, void* workspace, size_t workspace_bytes,
+                      void* stream);
 int moe_expert_ffn_down(const moe_config* cfg, const void* H, const int32_t* offsets,
-                        const void* W2, void* y_sliced, void* stream);
+                        const void* W2, void* y_sliced, void* workspace, size_t workspace_bytes,
+                        void* stream);
 int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
-                   const void* W1, const void* W2, void* H, void* y_sliced, void* stream);
+                   const void* W1, const void* W2, void* H, void* y_sliced, void* workspace,
+                   size_t workspace_bytes, void* stream);
 
 /* Combine (Sections 3.3.1/3.3.3, the index assignment that replaces the second all-to-all;
  * Algorithm 1: zeros_like + placement):
@@ -161,7 +170,7 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
 /* Where moe_layer_forward keeps its intermediates inside `workspace` (byte offsets), so a caller
  * can inspect them after a run.  Any pointer may be NULL. */
 typedef struct {
-  size_t expert_idx, gate_w, counts, offsets, perm, inv_perm, x_sliced, H, y_sliced, scratch;
+  size_t expert_idx, gate_w, counts, offsets, perm, inv_perm, x_sliced, H, y_sliced, scratch, gemm;
 } moe_workspace_layout;
 int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout);
 

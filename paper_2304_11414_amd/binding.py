@@ -24,7 +24,7 @@ class MoeConfig(Structure):
 
 class MoeWorkspaceLayout(Structure):
     _fields_ = [(n, c_size_t) for n in ("expert_idx", "gate_w", "counts", "offsets", "perm",
-                                        "inv_perm", "x_sliced", "H", "y_sliced", "scratch")]
+                                        "inv_perm", "x_sliced", "H", "y_sliced", "scratch", "gemm")]
 
 
 class MoeError(RuntimeError):
@@ -40,9 +40,10 @@ _PROTOTYPES = {
     "moe_workspace_offsets": (c_int, [POINTER(MoeConfig), POINTER(MoeWorkspaceLayout)]),
     "moe_gate": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8),
     "moe_slice_dispatch": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
-    "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
-    "moe_expert_ffn_down": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
-    "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7),
+    "moe_ffn_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
+    "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
+    "moe_expert_ffn_down": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
+    "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
     "moe_event_create": (c_int, [POINTER(c_void_p)]),
@@ -138,20 +139,30 @@ def moe_slice_dispatch(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sl
         _stream(stream)), "moe_slice_dispatch")
 
 
-def moe_expert_ffn_up(cfg, x_sliced, offsets, W1, H, stream=None):
+def moe_ffn_workspace_bytes(cfg) -> int:
+    return load_library().moe_ffn_workspace_bytes(byref(cfg))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def moe_expert_ffn_up(cfg, x_sliced, offsets, W1, H, workspace, stream=None):
     _check(load_library().moe_expert_ffn_up(byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1),
-                                            _ptr(H), _stream(stream)), "moe_expert_ffn_up")
+                                            _ptr(H), _ptr(workspace), _nbytes(workspace),
+                                            _stream(stream)), "moe_expert_ffn_up")
 
 
-def moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, stream=None):
+def moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, workspace, stream=None):
     _check(load_library().moe_expert_ffn_down(byref(cfg), _ptr(H), _ptr(offsets), _ptr(W2),
-                                              _ptr(y_sliced), _stream(stream)), "moe_expert_ffn_down")
+                                              _ptr(y_sliced), _ptr(workspace), _nbytes(workspace),
+                                              _stream(stream)), "moe_expert_ffn_down")
 
 
-def moe_expert_ffn(cfg, x_sliced, offsets, W1, W2, H, y_sliced, stream=None):
+def moe_expert_ffn(cfg, x_sliced, offsets, W1, W2, H, y_sliced, workspace, stream=None):
     _check(load_library().moe_expert_ffn(byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1),
-                                         _ptr(W2), _ptr(H), _ptr(y_sliced), _stream(stream)),
-           "moe_expert_ffn")
+                                         _ptr(W2), _ptr(H), _ptr(y_sliced), _ptr(workspace),
+                                         _nbytes(workspace), _stream(stream)), "moe_expert_ffn")
 
 
 def moe_combine(cfg, y_sliced, inv_perm, gate_w, out, stream=None):

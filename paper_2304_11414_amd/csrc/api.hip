@@ -72,6 +72,7 @@ void layout_of(const moe_config& c, moe_workspace_layout* L, size_t* total) {
   L->x_sliced = take(rows * c.d * eb);
   L->H = take(rows * c.F * eb);
   L->y_sliced = take(rows * c.d * eb);
+  L->gemm = take(grouped_gemm_workspace_bytes());
   *total = off;
 }
 
@@ -110,6 +111,11 @@ size_t moe_workspace_bytes(const moe_config* cfg) {
   size_t total = 0;
   layout_of(*cfg, &L, &total);
   return total;
+}
+
+size_t moe_ffn_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return 0;
+  return grouped_gemm_workspace_bytes();
 }
 
 size_t moe_dispatch_workspace_bytes(const moe_config* cfg) {
@@ -163,36 +169,47 @@ int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expe
 }
 
 int moe_expert_ffn_up(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
-                      const void* W1, void* H, void* stream) {
+                      const void* W1, void* H, void* workspace, size_t workspace_bytes,
+                      void* stream) {
   int st = check_config(cfg);
   if (st != MOE_OK) return st;
-  if (x_sliced == nullptr || offsets == nullptr || W1 == nullptr || H == nullptr) return MOE_ERR_NULL;
-  if (misaligned(x_sliced) || misaligned(offsets) || misaligned(W1) || misaligned(H))
+  if (x_sliced == nullptr || offsets == nullptr || W1 == nullptr || H == nullptr ||
+      workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(x_sliced) || misaligned(offsets) || misaligned(W1) || misaligned(H) ||
+      misaligned(workspace))
     return MOE_ERR_ALIGN;
+  if (workspace_bytes < grouped_gemm_workspace_bytes()) return MOE_ERR_WORKSPACE;
   return hip_status(launch_grouped_gemm(cfg->in_dtype, true, x_sliced, W1, H, offsets,
                                         cfg->local_count, max_rows_of(*cfg), cfg->F, cfg->d,
-                                        static_cast<hipStream_t>(stream)));
+                                        workspace, static_cast<hipStream_t>(stream)));
 }
 
 int moe_expert_ffn_down(const moe_config* cfg, const void* H, const int32_t* offsets,
-                        const void* W2, void* y_sliced, void* stream) {
+                        const void* W2, void* y_sliced, void* workspace, size_t workspace_bytes,
+                        void* stream) {
   int st = check_config(cfg);
   if (st != MOE_OK) return st;
-  if (H == nullptr || offsets == nullptr || W2 == nullptr || y_sliced == nullptr) return MOE_ERR_NULL;
-  if (misaligned(H) || misaligned(offsets) || misaligned(W2) || misaligned(y_sliced))
+  if (H == nullptr || offsets == nullptr || W2 == nullptr || y_sliced == nullptr ||
+      workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(H) || misaligned(offsets) || misaligned(W2) || misaligned(y_sliced) ||
+      misaligned(workspace))
     return MOE_ERR_ALIGN;
+  if (workspace_bytes < grouped_gemm_workspace_bytes()) return MOE_ERR_WORKSPACE;
   return hip_status(launch_grouped_gemm(cfg->in_dtype, false, H, W2, y_sliced, offsets,
                                         cfg->local_count, max_rows_of(*cfg), cfg->d, cfg->F,
-                                        static_cast<hipStream_t>(stream)));
+                                        workspace, static_cast<hipStream_t>(stream)));
 }
 
 int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
-                   const void* W1, const void* W2, void* H, void* y_sliced, void* stream) {
+                   const void* W1, const void* W2, void* H, void* y_sliced, void* workspace,
+                   size_t workspace_bytes, void* stream) {
   if (W2 == nullptr || y_sliced == nullptr) return MOE_ERR_NULL;
   if (misaligned(W2) || misaligned(y_sliced)) return MOE_ERR_ALIGN;
-  int st = moe_expert_ffn_up(cfg, x_sliced, offsets, W1, H, stream);
+  int st = moe_expert_ffn_up(cfg, x_sliced, offsets, W1, H, workspace, workspace_bytes, stream);
   if (st != MOE_OK) return st;
-  return moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, stream);
+  return moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, workspace, workspace_bytes, stream);
 }
 
 int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_perm,
@@ -260,10 +277,10 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
   PPMOE_TRY(launch_slice(c, x, perm, offsets, x_sliced, rows, s));
   PPMOE_TRY(mark(MOE_STAGE_FFN_UP));
   PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x_sliced, W1, H, offsets, c.local_count, rows, c.F,
-                                c.d, s));
+                                c.d, ws + L.gemm, s));
   PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
   PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, y_sliced, offsets, c.local_count, rows,
-                                c.d, c.F, s));
+                                c.d, c.F, ws + L.gemm, s));
   PPMOE_TRY(mark(MOE_STAGE_COMBINE));
   PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s));
   PPMOE_TRY(mark(MOE_NUM_STAGES));

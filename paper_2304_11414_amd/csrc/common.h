@@ -55,14 +55,18 @@ hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32
                           const float* gate_w, void* out, hipStream_t s);
 
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
+// workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
-                               hipStream_t s);
+                               void* workspace, hipStream_t s);
 
-// bf16 fast path of the above (K a multiple of 64).
+// bf16 fast path of the above (K a multiple of 64): persistent, at most kMaxPersistentBlocks blocks.
+constexpr int kMaxPersistentBlocks = 256;
+size_t grouped_gemm_fast_workspace_bytes();
+inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspace_bytes(); }
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
-                                    int K, hipStream_t s);
+                                    int K, void* workspace, hipStream_t s);
 
 inline int64_t n_segments(const moe_config& c) {
   int64_t a = static_cast<int64_t>(c.T) * c.top_k;

@@ -304,11 +304,11 @@ static hipError_t ensure_lds_attr() {
 
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
-                               hipStream_t s) {
+                               void* workspace, hipStream_t s) {
   if (max_rows == 0) return hipSuccess;
   if (in_dtype == MOE_BF16 && (K % 64) == 0) {
     return launch_grouped_gemm_fast(gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
-                                    static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, s);
+                                    static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s);
   }
   if (in_dtype == MOE_BF16) {
     hipError_t e = ensure_lds_attr();

@@ -21,8 +21,18 @@
 // cycle (16 consecutive rows, same logical piece) from 64 banks, and with this swizzle they touch 16
 // different 16-byte slots; so do the 16 lanes (2 rows x 8 pieces) of a ds_write_b128.
 //
+// Scheduling: the kernel is persistent (one block per CU).  The tile list (expert-major, then n-tile,
+// then m-tile) is cut into 8 contiguous runs of whole tiles, one per XCD (consecutive block ids go
+// round-robin over the XCDs), so the CUs sharing an L2 work on the same weight panels; inside an
+// XCD the run is treated as one stream of k-tiles and cut into equal shares, one per CU (stream-K):
+// no CU idles because the tile count is not a multiple of the CU count.  A tile cut between CUs is
+// finished by the CU that holds its first k-tile (the last thing that CU does); the others wrote
+// their partial accumulators to a scratch slot as the first thing they did and raised a flag.
+//
 // All LDS traffic is inline assembly with hand-counted lgkmcnt waits, so that the MFMA stream never
 // waits for more than it needs; global loads are plain loads (the compiler counts vmcnt for them).
+
+#include <atomic>
 
 #include "common.h"
 
@@ -46,6 +56,15 @@ __device__ __forceinline__ float gelu_tanh(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z2));
 }
 
+// Reads one accumulator element where it lives (an accumulator register), at this point of the
+// program: without it the compiler copies all 256 accumulators to vector registers right after the
+// K loop and spills half of them.
+__device__ __forceinline__ float read_acc(float a) {
+  float v;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
 template <int OFF>
 __device__ __forceinline__ void lds_read16(bf16x8& dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
@@ -62,18 +81,16 @@ struct Tile {
   int expert, row0, rows, col0;
 };
 
-// Tiles are ordered expert-major, then n-tile, then m-tile (m fastest), and the list is cut into 8
-// contiguous runs, one per XCD (consecutive block ids go round-robin over the XCDs), so that the
-// CUs sharing an L2 work on the same weight panels at the same time.
-__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int n_exp, int Nout,
-                                          int bid, Tile& t) {
-  const int n_tiles = (Nout + BN - 1) / BN;
+__device__ __forceinline__ int count_m_tiles(const int32_t* __restrict__ offsets, int n_exp) {
   int m_total = 0;
   for (int i = 0; i < n_exp; ++i) m_total += (offsets[i + 1] - offsets[i] + BM - 1) / BM;
-  const int total = m_total * n_tiles;
-  const int per = (total + 7) >> 3;
-  int tile = (bid & 7) * per + (bid >> 3);
-  if ((bid >> 3) >= per || tile >= total) return false;
+  return m_total;
+}
+
+// Tile `tile` of the list ordered expert-major, then n-tile, then m-tile (m fastest).
+__device__ __forceinline__ Tile tile_at(const int32_t* __restrict__ offsets, int n_exp, int n_tiles,
+                                        int tile) {
+  Tile t = {0, 0, 1, 0};
   int lo = offsets[0];
   for (int i = 0; i < n_exp; ++i) {
     const int hi = offsets[i + 1];
@@ -85,23 +102,24 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
       t.row0 = lo + mt * BM;
       t.rows = min(BM, hi - t.row0);
       t.col0 = nt * BN;
-      return true;
+      return t;
     }
     tile -= here;
     lo = hi;
   }
-  return false;
+  return t;
 }
+
+// Scratch for tiles cut between CUs: per block one slot of 256 x 256 float accumulators, one flag.
+constexpr int kSlotFloats = BM * BN;
+constexpr int kSpinLimit = 1 << 17;   // polls of a flag (a few tenths of a second) before giving up
 
 template <bool GELU>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
-    const int32_t* __restrict__ offsets, int n_exp, int Nout, int K) {
+    const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
+    uint32_t* __restrict__ flags, uint32_t epoch) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-
-  Tile tc;
-  if (!find_tile(offsets, n_exp, Nout, blockIdx.x, tc)) return;
-  const int cols = min(BN, Nout - tc.col0);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -109,22 +127,37 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
       (const __attribute__((address_space(3))) unsigned char*)lds));
 
-  // ---- global -> register -> LDS staging ---------------------------------------------------------
-  // A tile is 512 rows (256 token, 256 weight) of 128 bytes; one load instruction covers 8 rows, so a
-  // tile is 64 instructions, 16 per wavefront.  Wavefronts 0,1 fetch token rows, 2,3 weight rows;
-  // instruction n of a wavefront covers rows (wave & 1) * 128 + n * 8 .. + 8 of its operand.
+  // ---- this block's work -----------------------------------------------------------------------
+  // XCD x owns tiles [tx0, tx1) of the list.  With at least as many tiles as CUs, its `cus` CUs take
+  // whole tiles in rounds (round j: CU c takes tile tx0 + j*cus + c): neighbouring tiles run at the
+  // same time and in step along K, which is what lets the L2 serve a panel once for several CUs.
+  // With fewer tiles than CUs (few rows per expert, or a narrow output), the tiles become one stream
+  // of k-tiles cut into `cus` equal shares, so every CU has work; a tile is then finished by the CU
+  // that holds its first k-tile.  (Cutting the left-over tiles of a last, partial round this way was
+  // measured slower than running that round: the CUs fall out of step along K and the L2 hit rate
+  // drops, and the hand-over of partial sums costs about a tenth of a tile per cut.)
+  const int n_tiles = (Nout + BN - 1) / BN;
+  const int KT = K / BK;
+  const int total = count_m_tiles(offsets, n_exp) * n_tiles;
+  const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3, cus = gridDim.x >> 3;
+  const int tx0 = static_cast<int>(static_cast<int64_t>(total) * xcd / 8);
+  const int tx1 = static_cast<int>(static_cast<int64_t>(total) * (xcd + 1) / 8);
+  const int nt_x = tx1 - tx0;
+  const bool cut = nt_x < cus;
+  const int rounds = cut ? 0 : (nt_x + cus - 1) / cus;
+  const int ts0 = tx0;                                                  // first tile of the cut stream
+  const int64_t units = cut ? static_cast<int64_t>(nt_x) * KT : 0;
+  auto share_begin = [&](int c) -> int64_t { return units * c / cus; };
+  int round = 0;
+  int64_t u = share_begin(cu);
+  const int64_t u_end = share_begin(cu + 1);
+
+  // ---- addresses that do not depend on the tile ----------------------------------------------------
+  // Staging: a tile is 512 rows (256 token, 256 weight) of 128 bytes; one load instruction covers 8
+  // rows, so a tile is 64 instructions, 16 per wavefront.  Wavefronts 0,1 fetch token rows, 2,3
+  // weight rows; instruction n of a wavefront covers rows (wave & 1) * 128 + n * 8 .. + 8.
   const bool is_b = wave >= 2;
-  const unsigned char* gbase = reinterpret_cast<const unsigned char*>(
-      is_b ? B + (static_cast<size_t>(tc.expert) * Nout + tc.col0) * K
-           : A + static_cast<size_t>(tc.row0) * K);
-  const int row_lim = (is_b ? cols : tc.rows) - 1;
   const int lrow = lane >> 3, piece = lane & 7;
-  uint32_t goff[16];   // byte offset of this lane's piece in row n*8 + lrow (rows past the end re-read the last)
-#pragma unroll
-  for (int n = 0; n < 16; ++n) {
-    const int row = (wave & 1) * 128 + n * 8 + lrow;
-    goff[n] = (static_cast<uint32_t>(min(row, row_lim)) * K + piece * 8) * 2;
-  }
   // LDS write address: row*128 + swizzled piece; rows n*8 + lrow: (row >> 1) & 7 = (n & 1) * 4 + (lrow >> 1)
   uint32_t wr_addr[2];
 #pragma unroll
@@ -132,13 +165,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const int sw = (par * 4 + (lrow >> 1)) & 7;
     wr_addr[par] = lds0 + (is_b ? kOperandBytes : 0) + ((wave & 1) * 128 + lrow) * 128 + ((piece ^ sw) << 4);
   }
-  u32x4 stage[16];
-  auto gload = [&](int n, int t) {   // t: tile index along K
-    stage[n] = *reinterpret_cast<const u32x4*>(gbase + goff[n] + static_cast<size_t>(t) * (BK * 2));
-  };
-
-  // ---- MFMA operand addresses --------------------------------------------------------------------
-  // Lane holds row (lane & 31) of a 32-row fragment and the 8 k-values of piece 2*ks + (lane >> 5).
+  // MFMA operands: lane holds row (lane & 31) of a 32-row fragment and the 8 k-values of piece
+  // 2*ks + (lane >> 5).
   const int frow = lane & 31, half = lane >> 5;
   uint32_t tok_addr[4], wgt_addr[4];
 #pragma unroll
@@ -147,15 +175,15 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     tok_addr[ks] = lds0 + (wm * 128 + frow) * 128 + slot;
     wgt_addr[ks] = lds0 + kOperandBytes + (wn * 128 + frow) * 128 + slot;
   }
+  const uint32_t epi = lds0 + wave * (128 * 256);   // this wavefront's 32 KiB for the output transpose
 
+  const unsigned char* gbase;
+  uint32_t goff[16];   // byte offset of this lane's piece in row n*8 + lrow (rows past the end re-read the last)
+  u32x4 stage[16];
+  auto gload = [&](int n, int t) {   // t: tile index along K
+    stage[n] = *reinterpret_cast<const u32x4*>(gbase + goff[n] + static_cast<size_t>(t) * (BK * 2));
+  };
   f32x16 acc[4][4];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
   bf16x8 f0[8], f1[8];
 
 // The sched_barrier pins the hand-written interleaving of MFMAs and memory operations: without it
@@ -217,53 +245,202 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     if (DO_STAGE) gload(4 * Q + 3, LT);                                                              \
   } while (0)
 
-  const int KT = K / BK;
-  const int last = KT - 1;
 
-  // ---- prologue ----------------------------------------------------------------------------------
-  // Tile 0 goes through the registers into buffer 0; then tile 1 is loaded, its first quarter written
-  // to buffer 1 and replaced by the first quarter of tile 2: the state every loop iteration starts in.
-  // Tiles past the end of K are loaded from the last tile instead (never used), which keeps the loop
-  // free of branches.
+  while (round < rounds || u < u_end) {
+    // ---- one segment: k-tiles [kb, ke) of one output tile ---------------------------------------
+    int tl = 0, kb = 0, ke = KT, tile_index;
+    if (round < rounds) {
+      tile_index = tx0 + round * cus + cu;
+      ++round;
+      if (tile_index >= tx1) break;   // the last round may be partial
+    } else {
+      tl = static_cast<int>(u / KT);
+      kb = static_cast<int>(u - static_cast<int64_t>(tl) * KT);
+      ke = static_cast<int>(min(static_cast<int64_t>(KT), kb + (u_end - u)));
+      tile_index = ts0 + tl;
+      u += ke - kb;
+    }
+    const int last = ke - 1;
+    const Tile tc = tile_at(offsets, n_exp, n_tiles, tile_index);
+    const int cols = min(BN, Nout - tc.col0);
+    gbase = reinterpret_cast<const unsigned char*>(
+        is_b ? B + (static_cast<size_t>(tc.expert) * Nout + tc.col0) * K
+             : A + static_cast<size_t>(tc.row0) * K);
+    const int row_lim = (is_b ? cols : tc.rows) - 1;
 #pragma unroll
-  for (int n = 0; n < 16; ++n) gload(n, 0);
-  PPMOE_WRITE4(0, 0); PPMOE_WRITE4(1, 0); PPMOE_WRITE4(2, 0); PPMOE_WRITE4(3, 0);
+    for (int n = 0; n < 16; ++n) {
+      const int row = (wave & 1) * 128 + n * 8 + lrow;
+      goff[n] = (static_cast<uint32_t>(min(row, row_lim)) * K + piece * 8) * 2;
+    }
 #pragma unroll
-  for (int n = 0; n < 16; ++n) gload(n, min(1, last));
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  PPMOE_READ_TOK(f0, 0, 0, 0); PPMOE_READ_WGT(f0, 0, 0, 0);
-  PPMOE_READ_TOK(f0, 1, 0, 0); PPMOE_READ_WGT(f0, 1, 0, 0);
-  PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
-  PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
-  // (after the reads, so that the loop's first wait sees the same 8 reads + 4 writes as every other)
-  PPMOE_WRITE4(0, kBufBytes);
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-  for (int n = 0; n < 4; ++n) gload(n, min(2, last));
+      for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  // ---- main loop -----------------------------------------------------------------------------------
-  // At the top of tile t: buffer t&1 holds tile t (visible to all), f0 <- its k-step 0 (in flight),
-  // stage[4..15] hold quarters 1..3 of tile t+1 and stage[0..3] quarter 0 of tile t+2 (in flight),
-  // quarter 0 of tile t+1 is already in buffer (t+1)&1.
-  for (int t = 0; t < KT; ++t) {
-    const uint32_t rb = (t & 1) * kBufBytes, wb = kBufBytes - rb;
-    const int lt = min(t + 2, last);
-    // LDS operations complete in order: the 8 reads being waited for were always followed by exactly
-    // 4 writes, so "at most 4 outstanding" means the reads have landed.
-    asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
-    PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
-    asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f1)::"memory");
-    PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
-    asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
-    PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
-    // Every read of tile t and every write of tile t+1 by this wavefront has completed once
-    // lgkmcnt is 0; after the barrier that holds for the whole block.
-    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");
+    // ---- prologue --------------------------------------------------------------------------------
+    // The first tile goes through the registers into buffer 0; then the second is loaded, its first
+    // quarter written to buffer 1 and replaced by the first quarter of the third: the state every
+    // loop iteration starts in.  Tiles past the end of the segment are loaded from its last tile
+    // instead (never used), which keeps the loop free of branches.
+#pragma unroll
+    for (int n = 0; n < 16; ++n) gload(n, kb);
+    __builtin_amdgcn_s_barrier();   // the previous segment's output transpose is out of LDS
+    PPMOE_WRITE4(0, 0); PPMOE_WRITE4(1, 0); PPMOE_WRITE4(2, 0); PPMOE_WRITE4(3, 0);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) gload(n, min(kb + 1, last));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    // k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t is
-    // leaving, and is replaced in the registers by quarter 0 of tile t+3.
-    const int lt3 = min(t + 3, last);
-    PPMOE_STEP(f1, f0, 0, wb, 0, rb, lt3, true, true);
+    PPMOE_READ_TOK(f0, 0, 0, 0); PPMOE_READ_WGT(f0, 0, 0, 0);
+    PPMOE_READ_TOK(f0, 1, 0, 0); PPMOE_READ_WGT(f0, 1, 0, 0);
+    PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
+    PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
+    // (after the reads, so that the loop's first wait sees the same 8 reads + 4 writes as every other)
+    PPMOE_WRITE4(0, kBufBytes);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) gload(n, min(kb + 2, last));
+
+    // ---- main loop -------------------------------------------------------------------------------
+    // At the top of tile t (i = t - kb): buffer i&1 holds tile t (visible to all), f0 <- its k-step 0
+    // (in flight), stage[4..15] hold quarters 1..3 of tile t+1 and stage[0..3] quarter 0 of tile t+2
+    // (in flight), quarter 0 of tile t+1 is already in buffer (i+1)&1.
+    for (int t = kb; t < ke; ++t) {
+      const uint32_t rb = ((t - kb) & 1) * kBufBytes, wb = kBufBytes - rb;
+      const int lt = min(t + 2, last);
+      // LDS operations complete in order: the 8 reads being waited for were always followed by
+      // exactly 4 writes, so "at most 4 outstanding" means the reads have landed.
+      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+      PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
+      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f1)::"memory");
+      PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
+      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+      PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
+      // Every read of tile t and every write of tile t+1 by this wavefront has completed once
+      // lgkmcnt is 0; after the barrier that holds for the whole block.
+      asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");
+      __builtin_amdgcn_s_barrier();
+      // k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t
+      // is leaving, and is replaced in the registers by quarter 0 of tile t+3.
+      const int lt3 = min(t + 3, last);
+      PPMOE_STEP(f1, f0, 0, wb, 0, rb, lt3, true, true);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f0)::"memory");
+
+    // Per-segment opaque copies: they stop the compiler from hoisting the address arithmetic of the
+    // code below out of the segment loop, where it would cost a few hundred live registers.
+    uint32_t epi_l = epi;
+    int tid_l = tid;
+    asm volatile("" : "+v"(epi_l), "+v"(tid_l));
+
+    // A segment that does not hold the first k-tile of its output tile hands its partial sums to the
+    // CU that does (through this block's scratch slot); the one that holds it writes the output
+    // tile, after adding the partial sums of the CUs after it, if the rest of the k range went
+    // there (their first segment, which they finished long ago).
+    const bool partial_only = kb > 0;
+    f32x4* my_slot = reinterpret_cast<f32x4*>(slots + static_cast<size_t>(blockIdx.x) * kSlotFloats) + tid_l;
+    int c2_end = cu + 1;
+    if (!partial_only && ke < KT) {
+      while (c2_end < cus && share_begin(c2_end) < static_cast<int64_t>(tl + 1) * KT) ++c2_end;
+      if (tid == 0) {
+        // One thread polls (relaxed loads that go to L2, no cache maintenance inside the loop).
+        for (int c2 = cu + 1; c2 < c2_end; ++c2) {
+          if (share_begin(c2 + 1) == share_begin(c2)) continue;   // a CU with an empty share sends nothing
+          const uint32_t* flag = flags + ((c2 << 3) | xcd);
+          int spins = 0;
+          while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+            if (++spins >= kSpinLimit) {
+              flags[gridDim.x] = 1u;   // reported to the host; the result of this tile is incomplete
+              break;
+            }
+            __builtin_amdgcn_s_sleep(16);
+          }
+        }
+      }
+      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // once per thread, after the flags are up
+    }
+
+    // ---- epilogue --------------------------------------------------------------------------------
+    // D = W_frag (32 n) x Tok_frag^T (32 m): lane holds token m = lane & 31 and, in register v,
+    // output column n = (v / 4) * 8 + (lane >> 5) * 4 + v % 4: four consecutive columns per group.
+    // The 128 x 128 sub-tile of a wavefront goes through its own 32 KiB of LDS (rows of 256 bytes,
+    // 16-byte chunk c of row r at chunk c ^ (r & 15)) so that global stores are 16 bytes per lane
+    // and 256 contiguous bytes per row instead of 8-byte pieces scattered over 32 rows.
+    // The accumulators are read in exactly one place (one 32x32 block at a time), whichever way
+    // they go: that keeps them in the accumulator registers until then.
+    __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int ni = 0; ni < 4; ++ni) {
+        f32x4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[q][e] = read_acc(acc[mi][ni][q * 4 + e]);
+        if (partial_only) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) my_slot[((mi * 4 + ni) * 4 + q) * kThreads] = v[q];
+        } else {
+          for (int c2 = cu + 1; c2 < c2_end; ++c2) {   // partial sums, in CU order (fixed summation order)
+            if (share_begin(c2 + 1) == share_begin(c2)) continue;
+            const f32x4* slot =
+                reinterpret_cast<const f32x4*>(slots + static_cast<size_t>((c2 << 3) | xcd) * kSlotFloats) + tid_l;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] += slot[((mi * 4 + ni) * 4 + q) * kThreads];
+          }
+          const int r = mi * 32 + frow;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f32x4 w = v[q];
+            if (GELU) {
+              w[0] = gelu_tanh(w[0]);
+              w[1] = gelu_tanh(w[1]);
+              w[2] = gelu_tanh(w[2]);
+              w[3] = gelu_tanh(w[3]);
+            }
+            const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
+            const uint32_t a = epi_l + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
+            const uint32_t lo = pack_bf16x2(w[0], w[1]), hi = pack_bf16x2(w[2], w[3]);
+            asm volatile("ds_write_b64 %0, %1" : : "v"(a), "v"(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32)) : "memory");
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time keeps the register footprint small
+      }
+    }
+    if (partial_only) {
+      // Release: every thread makes its own stores visible device-wide, then the block meets, then
+      // one thread raises the flag (a relaxed store is enough after the fences).
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __syncthreads();
+      if (tid == 0)
+        __hip_atomic_store(flags + blockIdx.x, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      continue;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (c2_end > cu + 1) {
+      // every thread has read the partial sums: lower the flags (the scratch may be reused by a
+      // replay of the same launch, whose flags carry the same value)
+      __syncthreads();
+      if (tid == 0)
+        for (int c2 = cu + 1; c2 < c2_end; ++c2)
+          if (share_begin(c2 + 1) != share_begin(c2))
+            __hip_atomic_store(flags + ((c2 << 3) | xcd), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // Read back 16 bytes per lane: an instruction covers 4 rows x 256 bytes.
+    const int er = (tid_l & 63) >> 4, ec = tid_l & 15;
+    const int ncol = cols - wn * 128;   // valid columns of this wavefront's half (may be <= 0)
+    bf16_t* cbase = C + static_cast<size_t>(tc.row0 + wm * 128) * Nout + tc.col0 + wn * 128 + ec * 8;
+#pragma unroll 2
+    for (int i = 0; i < 32; ++i) {
+      const int r = i * 4 + er;
+      u32x4 v;
+      const uint32_t a = epi_l + r * 256 + ((ec ^ (r & 15)) << 4);
+      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+      if (wm * 128 + r < tc.rows && ec * 8 < ncol)
+        *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v;
+    }
   }
 #undef PPMOE_STEP
 #undef PPMOE_WRITE4
@@ -271,77 +448,54 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #undef PPMOE_READ_TOK
 #undef PPMOE_READ_WGT
 #undef PPMOE_MFMA
-  asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f0)::"memory");
-
-  // ---- epilogue ----------------------------------------------------------------------------------
-  // D = W_frag (32 n) x Tok_frag^T (32 m): lane holds token m = lane & 31 and, in register v, output
-  // column n = (v / 4) * 8 + (lane >> 5) * 4 + v % 4: four consecutive columns per group of 4.
-  // The 128 x 128 sub-tile of a wavefront goes through its own 32 KiB of LDS (rows of 256 bytes,
-  // 16-byte chunk c of row r at chunk c ^ (r & 15)) so that global stores are 16 bytes per lane and
-  // 256 contiguous bytes per row instead of 8-byte pieces scattered over 32 rows.
-  __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
-  const uint32_t epi = lds0 + wave * (128 * 256);
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
-    const int r = mi * 32 + frow;
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float v0 = acc[mi][ni][q * 4 + 0], v1 = acc[mi][ni][q * 4 + 1];
-        float v2 = acc[mi][ni][q * 4 + 2], v3 = acc[mi][ni][q * 4 + 3];
-        if (GELU) {
-          v0 = gelu_tanh(v0);
-          v1 = gelu_tanh(v1);
-          v2 = gelu_tanh(v2);
-          v3 = gelu_tanh(v3);
-        }
-        const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
-        const uint32_t a = epi + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
-        const uint32_t lo = pack_bf16x2(v0, v1), hi = pack_bf16x2(v2, v3);
-        asm volatile("ds_write_b64 %0, %1" : : "v"(a), "v"(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32)) : "memory");
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);   // one row block at a time keeps the register footprint small
-  }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  // Read back 16 bytes per lane: an instruction covers 4 rows x 256 bytes.
-  const int er = lane >> 4, ec = lane & 15;
-  const int ncol = cols - wn * 128;   // valid columns of this wavefront's half (may be <= 0)
-#pragma unroll 4
-  for (int i = 0; i < 32; ++i) {
-    const int r = i * 4 + er;
-    u32x4 v;
-    const uint32_t a = epi + r * 256 + ((ec ^ (r & 15)) << 4);
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
-    const int m = wm * 128 + r;
-    if (m < tc.rows && ec * 8 < ncol)
-      *reinterpret_cast<u32x4*>(C + static_cast<size_t>(tc.row0 + m) * Nout + tc.col0 + wn * 128 + ec * 8) = v;
-  }
 }
 
 }  // namespace fast
 
+size_t grouped_gemm_fast_workspace_bytes() {
+  return static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats * sizeof(float) +
+         (kMaxPersistentBlocks + 1) * sizeof(uint32_t) + 256;
+}
+
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
-                                    int K, hipStream_t s) {
+                                    int K, void* workspace, hipStream_t s) {
   using namespace fast;
-  static hipError_t attr = [] {
-    hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  struct Setup {
+    hipError_t err;
+    int blocks;
+  };
+  static const Setup setup = [] {
+    Setup r{hipSuccess, 0};
+    r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (r.err != hipSuccess) return r;
+    r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (r.err != hipSuccess) return r;
+    int dev = 0, cus = 0;
+    r.err = hipGetDevice(&dev);
+    if (r.err != hipSuccess) return r;
+    r.err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (r.err != hipSuccess) return r;
+    if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
+    r.blocks = cus & ~7;   // one block per CU, the same number on each of the 8 XCDs
+    if (r.blocks < 8) r.err = hipErrorInvalidConfiguration;
+    return r;
   }();
-  if (attr != hipSuccess) return attr;
-  const int64_t m_tiles = (max_rows + BM - 1) / BM + n_exp;   // upper bound on the sum of ceilings
-  const int64_t n_tiles = (Nout + BN - 1) / BN;
-  const unsigned grid = static_cast<unsigned>(((m_tiles * n_tiles + 7) / 8) * 8);
+  if (setup.err != hipSuccess) return setup.err;
+  static std::atomic<uint32_t> launches{0};
+  uint32_t epoch = ++launches;
+  if (epoch == 0) epoch = ++launches;   // 0 means "flag down"
+  float* slots = static_cast<float*>(workspace);
+  uint32_t* flags = reinterpret_cast<uint32_t*>(slots + static_cast<size_t>(kMaxPersistentBlocks) * kSlotFloats);
+  (void)max_rows;
   if (gelu)
-    grouped_gemm_bf16_fast_kernel<true><<<grid, kThreads, kLdsBytes, s>>>(A, B, C, offsets, n_exp, Nout, K);
+    grouped_gemm_bf16_fast_kernel<true><<<setup.blocks, kThreads, kLdsBytes, s>>>(
+        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch);
   else
-    grouped_gemm_bf16_fast_kernel<false><<<grid, kThreads, kLdsBytes, s>>>(A, B, C, offsets, n_exp, Nout, K);
+    grouped_gemm_bf16_fast_kernel<false><<<setup.blocks, kThreads, kLdsBytes, s>>>(
+        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch);
   return hipGetLastError();
 }
 

@@ -122,7 +122,8 @@ class DeviceLayer:
         off = to_dev(np.asarray(offsets, dtype=np.int32))
         H = self.empty((max(self.rows, 1), c.F), et)
         y = self.empty((max(self.rows, 1), c.d), et)
-        B.moe_expert_ffn(c, xs, off, self.W1, self.W2, H, y)
+        ws = self.empty((B.moe_ffn_workspace_bytes(c),), t.uint8)
+        B.moe_expert_ffn(c, xs, off, self.W1, self.W2, H, y, ws)
         t.cuda.synchronize()
         return to_np(H[:n]), to_np(y[:n])
 
