@@ -26,6 +26,23 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "grouped_gemm_gpt_top1_hbm_traffic.txt")
+
+
+def measured_traffic(workload, stage):
+    """HBM bytes per launch of one of the grouped GEMMs ("ffn_up" / "ffn_down"), from the committed
+    rocprofv3 --pmc summary (the counters cannot be read from inside this process).  None when
+    there is no summary for this workload."""
+    try:
+        text = open(TRAFFIC_FILE).read()
+    except OSError:
+        return None
+    if f"workload: {workload}" not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith(f"traffic_bytes_per_launch[{stage}]:"):
+            return float(line.split(":")[1])
+    return None
 
 
 def log(*a):
@@ -59,8 +76,11 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into synth.CONFIGS (1 = headline)")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens the CPU oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB (reference of known "
+                         "traffic for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -93,6 +113,14 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(3):
+            B.moe_copy_bytes(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     K = args.steps
     events = [[B.moe_event_create() for _ in range(B.MOE_NUM_STAGES + 1)] for _ in range(K)]
@@ -146,6 +174,10 @@ def main():
         "combine_frac_of_hbm_peak": round(bytes_combine / (st["combine"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
     }
     log("[bench] " + json.dumps(detail))
+    # The dominant kernel is whichever of the two grouped GEMMs (same kernel template, equal FLOPs)
+    # takes longer.
+    dom = "ffn_up" if st["ffn_up"] >= st["ffn_down"] else "ffn_down"
+    dom_tflops = tflops_up if dom == "ffn_up" else tflops_dn
 
     result = {
         "metric": "MoE-layer fwd tokens/s at d=2048,E=8,top-1 bf16; % MFMA peak (GEMM), % HBM (slice)",
@@ -158,9 +190,9 @@ def main():
         "config": {"workload": f"{lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
                                f"top_k={lc.top_k} capacity_factor={lc.capacity_factor} "
                                f"{lc.in_dtype} in / {lc.out_dtype} out, seed {lc.seed}"},
-        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<GELU> (ffn_up)",
-                     "achieved": tflops_up, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops_up / PEAK_BF16_TFLOPS, "traffic": None},
+        "roofline": {"bound": "mfma", "kernel": f"grouped_gemm_bf16_fast_kernel ({dom})",
+                     "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": measured_traffic(lc.name, dom)},
         "detail": detail,
     }
     if not args.no_cpu_baseline:

@@ -174,6 +174,11 @@ typedef struct {
 } moe_workspace_layout;
 int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16) by a kernel that reads and writes
+ * every byte exactly once.  Not part of the layer: it is the reference of known traffic against
+ * which hardware byte counters (FETCH_SIZE, WRITE_SIZE) are calibrated when profiling. */
+int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Timing helpers: thin wrappers over hipEvent so a caller without HIP headers can time stages.
  * moe_event_elapsed_ms synchronises on `stop` before reading. */
 int moe_event_create(void** event);

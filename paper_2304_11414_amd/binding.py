@@ -46,6 +46,7 @@ _PROTOTYPES = {
     "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
+    "moe_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
     "moe_event_create": (c_int, [POINTER(c_void_p)]),
     "moe_event_destroy": (c_int, [c_void_p]),
     "moe_event_record": (c_int, [c_void_p, c_void_p]),
@@ -178,6 +179,11 @@ def moe_layer_forward(cfg, x, Wg, bias, W1, W2, out, workspace, stage_events=Non
     _check(load_library().moe_layer_forward(
         byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), ev, _stream(stream)), "moe_layer_forward")
+
+
+def moe_copy_bytes(src, dst, stream=None):
+    _check(load_library().moe_copy_bytes(_ptr(src), _ptr(dst), _nbytes(src), _stream(stream)),
+           "moe_copy_bytes")
 
 
 def moe_event_create() -> int:

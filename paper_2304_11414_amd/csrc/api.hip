@@ -288,6 +288,14 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
   return MOE_OK;
 }
 
+int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {
+  if (src == nullptr || dst == nullptr) return MOE_ERR_NULL;
+  if (misaligned(src) || misaligned(dst)) return MOE_ERR_ALIGN;
+  if (bytes % 16 != 0) return MOE_ERR_SHAPE;
+  return hip_status(launch_copy_bytes(src, dst, static_cast<int64_t>(bytes),
+                                      static_cast<hipStream_t>(stream)));
+}
+
 int moe_event_create(void** event) {
   if (event == nullptr) return MOE_ERR_NULL;
   hipEvent_t ev;

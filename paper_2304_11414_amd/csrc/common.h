@@ -11,7 +11,7 @@ namespace ppmoe {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxExperts = 256;   // E limit of the ABI
 constexpr int kMaxTopK = 8;
-constexpr int kSegment = 512;      // assignments ranked by one wavefront in the permutation
+constexpr int kSegment = 64;       // assignments ranked by one wavefront in the permutation
 
 typedef uint16_t bf16_t;           // raw bf16 bits in memory
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte piece
@@ -53,6 +53,8 @@ hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
 
 hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
                           const float* gate_w, void* out, hipStream_t s);
+
+hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t s);
 
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
 // workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).

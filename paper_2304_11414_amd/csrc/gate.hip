@@ -85,28 +85,34 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // U spans of 128 k-values per iteration: all their loads are issued before the first MFMA, so a
+  // wavefront keeps U * (MT + NT) * 4 16-byte loads in flight.
+  constexpr int U = (NT * MT <= 4) ? 2 : 1;
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-  for (int c0 = wave * 16; c0 < nchunk; c0 += 64) {
-    u32x4 a[MT][4];
+  for (int c0 = wave * 16; c0 < nchunk; c0 += 64 * U) {
+    u32x4 a[U][MT][4], b[U][NT][4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int c = c0 + i * 4 + g;
-        a[mt][i] = c < nchunk ? __builtin_nontemporal_load(xrow[mt] + c) : zero;
-      }
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
+    for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        int c = c0 + i * 4 + g;
-        u32x4 b = c < nchunk ? wrow[nt][c] : zero;
+        const int c = c0 + u * 64 + i * 4 + g;
+        const bool ok = c < nchunk;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8, a[mt][i]), __builtin_bit_cast(bf16x8, b), acc[mt][nt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) a[u][mt][i] = ok ? __builtin_nontemporal_load(xrow[mt] + c) : zero;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) b[u][nt][i] = ok ? wrow[nt][c] : zero;
       }
-    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, a[u][mt][i]), __builtin_bit_cast(bf16x8, b[u][nt][i]),
+                acc[mt][nt], 0, 0, 0);
   }
 
   // D layout of the 16x16 MFMA: lane holds column (lane % 16), rows (lane / 16) * 4 + i.

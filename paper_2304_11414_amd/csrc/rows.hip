@@ -6,7 +6,7 @@
 //              (Algorithm 1: zeros_like + index assignment).  It is written as a gather per output
 //              row, so each row of `out` is stored exactly once, zeros included: no atomics, no
 //              separate memset, bitwise reproducible.
-// Rows are moved as 16-byte pieces; a block owns kRowsPerBlock rows per iteration so that enough
+// Rows are moved as 16-byte pieces; a block owns kRowsPerIter rows per iteration so that enough
 // loads are in flight per CU.
 
 #include "common.h"
@@ -17,30 +17,35 @@ constexpr int kCopyThreads = 256;
 
 // ---- slice ------------------------------------------------------------------------------------
 
+constexpr int kRowsPerIter = 4;   // rows a block moves per iteration: 4 x 16 bytes in flight per thread
+
 __global__ __launch_bounds__(kCopyThreads) void slice_rows_kernel(
     const u32x4* __restrict__ x, const int32_t* __restrict__ perm,
     const int32_t* __restrict__ offsets, u32x4* __restrict__ x_sliced, int n_local, int top_k,
-    int chunks_per_row /* d * sizeof(elem) / 16 */) {
+    int chunks_per_row /* d * sizeof(elem) / 16 */, int max_rows, int T) {
+  // The row count lives on the device.  It is not waited for before the first loads go out: perm is
+  // read for every row below max_rows (stale entries past the real count are clamped to a valid
+  // token and their copies dropped at the store), so the loads of offsets, perm and x overlap.
   const int total_rows = offsets[n_local];
-  const int64_t total_chunks = static_cast<int64_t>(total_rows) * chunks_per_row;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kCopyThreads * 4;
-  for (int64_t c0 = (static_cast<int64_t>(blockIdx.x) * 4) * kCopyThreads + threadIdx.x;
-       c0 < total_chunks; c0 += stride) {
-    u32x4 v[4];
-    int64_t c[4];
+  for (int r0 = blockIdx.x * kRowsPerIter; r0 < max_rows; r0 += gridDim.x * kRowsPerIter) {
+    const u32x4* src[kRowsPerIter];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      c[i] = c0 + static_cast<int64_t>(i) * kCopyThreads;
-      if (c[i] < total_chunks) {
-        int r = static_cast<int>(c[i] / chunks_per_row);
-        int col = static_cast<int>(c[i] - static_cast<int64_t>(r) * chunks_per_row);
-        int t = perm[r] / top_k;
-        v[i] = __builtin_nontemporal_load(x + static_cast<int64_t>(t) * chunks_per_row + col);
-      }
+    for (int i = 0; i < kRowsPerIter; ++i) {
+      const int r = min(r0 + i, max_rows - 1);
+      const int a = perm[r];
+      const int t = top_k == 1 ? a : a / top_k;
+      src[i] = x + static_cast<int64_t>(min(max(t, 0), T - 1)) * chunks_per_row;
     }
+    for (int col = threadIdx.x; col < chunks_per_row; col += kCopyThreads) {
+      u32x4 v[kRowsPerIter];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (c[i] < total_chunks) __builtin_nontemporal_store(v[i], x_sliced + c[i]);
+      for (int i = 0; i < kRowsPerIter; ++i) v[i] = __builtin_nontemporal_load(src[i] + col);
+#pragma unroll
+      for (int i = 0; i < kRowsPerIter; ++i)
+        if (r0 + i < total_rows)
+          __builtin_nontemporal_store(v[i], x_sliced + static_cast<int64_t>(r0 + i) * chunks_per_row + col);
+    }
+    if (r0 + gridDim.x * kRowsPerIter >= total_rows) break;   // uniform: nothing left for this block
   }
 }
 
@@ -49,12 +54,31 @@ hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
   if (max_rows == 0 || c.T == 0) return hipSuccess;
   const int elem = c.in_dtype == MOE_BF16 ? 2 : 4;
   const int chunks_per_row = c.d * elem / 16;
-  int64_t max_chunks = max_rows * chunks_per_row;
-  int64_t want = (max_chunks + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
-  int blocks = static_cast<int>(want < 256 * 16 ? want : 256 * 16);
+  int64_t want = (max_rows + kRowsPerIter - 1) / kRowsPerIter;
+  int blocks = static_cast<int>(want < 256 * 8 ? want : 256 * 8);
   slice_rows_kernel<<<blocks, kCopyThreads, 0, s>>>(
       static_cast<const u32x4*>(x), perm, offsets, static_cast<u32x4*>(x_sliced), c.local_count,
-      c.top_k, chunks_per_row);
+      c.top_k, chunks_per_row, static_cast<int>(max_rows), c.T);
+  return hipGetLastError();
+}
+
+// ---- plain copy (reference kernel of known traffic, for calibrating hardware byte counters) ----
+
+__global__ __launch_bounds__(kCopyThreads) void copy_bytes_kernel(const u32x4* __restrict__ src,
+                                                                  u32x4* __restrict__ dst,
+                                                                  int64_t pieces) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kCopyThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kCopyThreads + threadIdx.x; i < pieces; i += stride)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t s) {
+  const int64_t pieces = bytes / 16;
+  if (pieces == 0) return hipSuccess;
+  int64_t want = (pieces + kCopyThreads - 1) / kCopyThreads;
+  int blocks = static_cast<int>(want < 256 * 16 ? want : 256 * 16);
+  copy_bytes_kernel<<<blocks, kCopyThreads, 0, s>>>(static_cast<const u32x4*>(src),
+                                                    static_cast<u32x4*>(dst), pieces);
   return hipGetLastError();
 }
 
@@ -85,47 +109,53 @@ struct Elems<float> {
   }
 };
 
-// One thread produces Elems<TIn>::n consecutive output elements of one token.
+// A block produces kRowsPerIter output rows per iteration; a thread, 16 bytes of y per pick and the
+// matching Elems<TIn>::n output elements of each of those rows.
 template <typename TIn, typename TOut>
 __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
     const u32x4* __restrict__ y, const int32_t* __restrict__ inv_perm,
     const float* __restrict__ gate_w, TOut* __restrict__ out, int T, int d, int top_k) {
   constexpr int n = Elems<TIn>::n;
   const int pieces_per_row = d / n;
-  const int64_t total = static_cast<int64_t>(T) * pieces_per_row;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kCopyThreads;
-  for (int64_t p = static_cast<int64_t>(blockIdx.x) * kCopyThreads + threadIdx.x; p < total;
-       p += stride) {
-    const int t = static_cast<int>(p / pieces_per_row);
-    const int col = static_cast<int>(p - static_cast<int64_t>(t) * pieces_per_row);
-    float acc[n];
+  for (int t0 = blockIdx.x * kRowsPerIter; t0 < T; t0 += gridDim.x * kRowsPerIter) {
+    for (int col = threadIdx.x; col < pieces_per_row; col += kCopyThreads) {
+      float acc[kRowsPerIter][n];
 #pragma unroll
-    for (int i = 0; i < n; ++i) acc[i] = 0.f;
-    for (int j = 0; j < top_k; ++j) {
-      const int r = inv_perm[static_cast<int64_t>(t) * top_k + j];
-      if (r >= 0) {
-        const float w = gate_w[static_cast<int64_t>(t) * top_k + j];
-        float f[n];
-        Elems<TIn>::widen(
-            __builtin_nontemporal_load(y + static_cast<int64_t>(r) * pieces_per_row + col), f);
+      for (int i = 0; i < kRowsPerIter; ++i) {
 #pragma unroll
-        for (int i = 0; i < n; ++i) acc[i] = fmaf(w, f[i], acc[i]);
+        for (int e = 0; e < n; ++e) acc[i][e] = 0.f;
+        const int t = min(t0 + i, T - 1);
+        for (int j = 0; j < top_k; ++j) {
+          const int r = inv_perm[static_cast<int64_t>(t) * top_k + j];
+          if (r >= 0) {
+            const float w = gate_w[static_cast<int64_t>(t) * top_k + j];
+            float f[n];
+            Elems<TIn>::widen(
+                __builtin_nontemporal_load(y + static_cast<int64_t>(r) * pieces_per_row + col), f);
+#pragma unroll
+            for (int e = 0; e < n; ++e) acc[i][e] = fmaf(w, f[e], acc[i][e]);
+          }
+        }
       }
-    }
-    TOut* o = out + static_cast<int64_t>(t) * d + static_cast<int64_t>(col) * n;
-    if constexpr (sizeof(TOut) == 2) {
-      static_assert(n == 8, "bf16 output comes from bf16 input");
-      u32x4 v;
-      v.x = pack_bf16x2(acc[0], acc[1]);
-      v.y = pack_bf16x2(acc[2], acc[3]);
-      v.z = pack_bf16x2(acc[4], acc[5]);
-      v.w = pack_bf16x2(acc[6], acc[7]);
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(o));
-    } else {
 #pragma unroll
-      for (int i = 0; i < n; i += 4) {
-        f32x4 v = {acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(o + i));
+      for (int i = 0; i < kRowsPerIter; ++i) {
+        if (t0 + i >= T) continue;
+        TOut* o = out + static_cast<int64_t>(t0 + i) * d + static_cast<int64_t>(col) * n;
+        if constexpr (sizeof(TOut) == 2) {
+          static_assert(n == 8, "bf16 output comes from bf16 input");
+          u32x4 v;
+          v.x = pack_bf16x2(acc[i][0], acc[i][1]);
+          v.y = pack_bf16x2(acc[i][2], acc[i][3]);
+          v.z = pack_bf16x2(acc[i][4], acc[i][5]);
+          v.w = pack_bf16x2(acc[i][6], acc[i][7]);
+          __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(o));
+        } else {
+#pragma unroll
+          for (int e = 0; e < n; e += 4) {
+            f32x4 v = {acc[i][e], acc[i][e + 1], acc[i][e + 2], acc[i][e + 3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(o + e));
+          }
+        }
       }
     }
   }
@@ -135,9 +165,9 @@ hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32
                           const float* gate_w, void* out, hipStream_t s) {
   if (c.T == 0) return hipSuccess;
   const int n = c.in_dtype == MOE_BF16 ? 8 : 4;
-  int64_t total = static_cast<int64_t>(c.T) * (c.d / n);
-  int64_t want = (total + kCopyThreads - 1) / kCopyThreads;
-  int blocks = static_cast<int>(want < 256 * 32 ? want : 256 * 32);
+  (void)n;
+  int64_t want = (static_cast<int64_t>(c.T) + kRowsPerIter - 1) / kRowsPerIter;
+  int blocks = static_cast<int>(want < 256 * 8 ? want : 256 * 8);
   const u32x4* y = static_cast<const u32x4*>(y_sliced);
   if (c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16)
     combine_kernel<bf16_t, bf16_t><<<blocks, kCopyThreads, 0, s>>>(
