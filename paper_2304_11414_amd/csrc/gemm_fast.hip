@@ -81,23 +81,44 @@ struct Tile {
   int expert, row0, rows, col0;
 };
 
-__device__ __forceinline__ int count_m_tiles(const int32_t* __restrict__ offsets, int n_exp) {
-  int m_total = 0;
-  for (int i = 0; i < n_exp; ++i) m_total += (offsets[i + 1] - offsets[i] + BM - 1) / BM;
-  return m_total;
+// An expert's rows are cut into m-tiles of BM; its last m-tile is "small" when it has at most
+// kSmallRows rows.  The tile list has two parts: all the other ("big") tiles, ordered expert-major,
+// then n-tile, then m-tile (m fastest); then the small tiles, ordered expert-major, then n-tile.
+// (Only when K is long: with a short K loop the hand-over of partial sums costs more than letting
+// the tail tile take a slot of a round; measured on K = 2048 against K = 8192.)
+constexpr int kSmallRows = 128;
+constexpr int kSmallMinKTiles = 64;
+constexpr int kMinShare = 16;   // k-tiles: the smallest share of a cut stream a CU is given
+
+__device__ __forceinline__ void expert_tiles(int cnt, int small_rows, int& big_m, int& small) {
+  const int m_tiles = (cnt + BM - 1) / BM;
+  small = (m_tiles > 0 && cnt - (m_tiles - 1) * BM <= small_rows) ? 1 : 0;
+  big_m = m_tiles - small;
 }
 
-// Tile `tile` of the list ordered expert-major, then n-tile, then m-tile (m fastest).
-__device__ __forceinline__ Tile tile_at(const int32_t* __restrict__ offsets, int n_exp, int n_tiles,
-                                        int tile) {
+__device__ __forceinline__ void count_tiles(const int32_t* __restrict__ offsets, int n_exp,
+                                            int n_tiles, int small_rows, int& total_big,
+                                            int& total_small) {
+  total_big = total_small = 0;
+  for (int i = 0; i < n_exp; ++i) {
+    int big_m, small;
+    expert_tiles(offsets[i + 1] - offsets[i], small_rows, big_m, small);
+    total_big += big_m * n_tiles;
+    total_small += small * n_tiles;
+  }
+}
+
+__device__ __forceinline__ Tile big_tile_at(const int32_t* __restrict__ offsets, int n_exp,
+                                            int n_tiles, int small_rows, int tile) {
   Tile t = {0, 0, 1, 0};
   int lo = offsets[0];
   for (int i = 0; i < n_exp; ++i) {
     const int hi = offsets[i + 1];
-    const int m_tiles = (hi - lo + BM - 1) / BM;
-    const int here = m_tiles * n_tiles;
+    int big_m, small;
+    expert_tiles(hi - lo, small_rows, big_m, small);
+    const int here = big_m * n_tiles;
     if (tile < here) {
-      const int nt = tile / m_tiles, mt = tile - nt * m_tiles;
+      const int nt = tile / big_m, mt = tile - nt * big_m;
       t.expert = i;
       t.row0 = lo + mt * BM;
       t.rows = min(BM, hi - t.row0);
@@ -105,6 +126,29 @@ __device__ __forceinline__ Tile tile_at(const int32_t* __restrict__ offsets, int
       return t;
     }
     tile -= here;
+    lo = hi;
+  }
+  return t;
+}
+
+__device__ __forceinline__ Tile small_tile_at(const int32_t* __restrict__ offsets, int n_exp,
+                                              int n_tiles, int small_rows, int tile) {
+  Tile t = {0, 0, 1, 0};
+  int lo = offsets[0];
+  for (int i = 0; i < n_exp; ++i) {
+    const int hi = offsets[i + 1];
+    int big_m, small;
+    expert_tiles(hi - lo, small_rows, big_m, small);
+    if (small) {
+      if (tile < n_tiles) {
+        t.expert = i;
+        t.row0 = lo + big_m * BM;
+        t.rows = hi - t.row0;
+        t.col0 = tile * BN;
+        return t;
+      }
+      tile -= n_tiles;
+    }
     lo = hi;
   }
   return t;
@@ -120,6 +164,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
     uint32_t* __restrict__ flags, uint32_t epoch) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,26 +173,35 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       (const __attribute__((address_space(3))) unsigned char*)lds));
 
   // ---- this block's work -----------------------------------------------------------------------
-  // XCD x owns tiles [tx0, tx1) of the list.  With at least as many tiles as CUs, its `cus` CUs take
-  // whole tiles in rounds (round j: CU c takes tile tx0 + j*cus + c): neighbouring tiles run at the
-  // same time and in step along K, which is what lets the L2 serve a panel once for several CUs.
-  // With fewer tiles than CUs (few rows per expert, or a narrow output), the tiles become one stream
-  // of k-tiles cut into `cus` equal shares, so every CU has work; a tile is then finished by the CU
-  // that holds its first k-tile.  (Cutting the left-over tiles of a last, partial round this way was
-  // measured slower than running that round: the CUs fall out of step along K and the L2 hit rate
-  // drops, and the hand-over of partial sums costs about a tenth of a tile per cut.)
+  // Each XCD owns a contiguous eighth of the big tiles and an eighth of the small tiles (consecutive
+  // block ids go round-robin over the 8 XCDs, so `cus` = gridDim/8 blocks share an L2).
+  //  * With at least `cus` big tiles, its CUs take them whole, in rounds (round j: CU c takes big
+  //    tile j*cus + c of the XCD's run): neighbouring tiles run at the same time and in step along
+  //    K, which is what lets the L2 serve a panel once for several CUs.
+  //  * The small tiles -- and the big ones too when there are fewer than `cus` of them (few rows
+  //    per expert, or a narrow output) -- form one stream of k-tiles that is cut into `cus` equal
+  //    shares, so that a 3-row tail of an expert does not cost a CU a whole tile slot and every CU
+  //    has work.  A tile cut this way is finished by the CU that holds its first k-tile.
+  // (Cutting the left-over big tiles of a last, partial round the same way was measured slower than
+  // running that round: the CUs fall out of step along K, the L2 hit rate drops, and handing over
+  // 256 KiB of partial sums costs about a tenth of a short tile per cut.)
   const int n_tiles = (Nout + BN - 1) / BN;
   const int KT = K / BK;
-  const int total = count_m_tiles(offsets, n_exp) * n_tiles;
+  int total_big, total_small;
+  const int small_rows = KT >= kSmallMinKTiles ? kSmallRows : 0;
+  count_tiles(offsets, n_exp, n_tiles, small_rows, total_big, total_small);
   const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3, cus = gridDim.x >> 3;
-  const int tx0 = static_cast<int>(static_cast<int64_t>(total) * xcd / 8);
-  const int tx1 = static_cast<int>(static_cast<int64_t>(total) * (xcd + 1) / 8);
-  const int nt_x = tx1 - tx0;
-  const bool cut = nt_x < cus;
-  const int rounds = cut ? 0 : (nt_x + cus - 1) / cus;
-  const int ts0 = tx0;                                                  // first tile of the cut stream
-  const int64_t units = cut ? static_cast<int64_t>(nt_x) * KT : 0;
-  auto share_begin = [&](int c) -> int64_t { return units * c / cus; };
+  const int bx0 = static_cast<int>(static_cast<int64_t>(total_big) * xcd / 8);
+  const int bx1 = static_cast<int>(static_cast<int64_t>(total_big) * (xcd + 1) / 8);
+  const int sx0 = static_cast<int>(static_cast<int64_t>(total_small) * xcd / 8);
+  const int sx1 = static_cast<int>(static_cast<int64_t>(total_small) * (xcd + 1) / 8);
+  const bool cut_big = bx1 - bx0 < cus;
+  const int rounds = cut_big ? 0 : (bx1 - bx0 + cus - 1) / cus;
+  const int stream_big = cut_big ? bx1 - bx0 : 0;                  // big tiles at the head of the stream
+  const int64_t units = static_cast<int64_t>(stream_big + sx1 - sx0) * KT;
+  // Shares shorter than kMinShare k-tiles are not worth their hand-over: fewer CUs then take part.
+  const int takers = static_cast<int>(max(static_cast<int64_t>(1), min(static_cast<int64_t>(cus), units / kMinShare)));
+  auto share_begin = [&](int c) -> int64_t { return units * min(c, takers) / takers; };
   int round = 0;
   int64_t u = share_begin(cu);
   const int64_t u_end = share_begin(cu + 1);
@@ -192,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #define PPMOE_MFMA(f, mi, ni)                                                                        \
   do {                                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
-    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[4 + ni], f[mi], acc[mi][ni], 0, 0, 0); \
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[4 + ni], f[mi], acc[mi][ni], 0, 0, 0); \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define PPMOE_READ_TOK(f, i, ks, buf) lds_read16<i * 4096>(f[i], tok_addr[ks] + (buf))
@@ -248,20 +302,22 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 
   while (round < rounds || u < u_end) {
     // ---- one segment: k-tiles [kb, ke) of one output tile ---------------------------------------
-    int tl = 0, kb = 0, ke = KT, tile_index;
+    int tl = 0, kb = 0, ke = KT;
+    Tile tc;
     if (round < rounds) {
-      tile_index = tx0 + round * cus + cu;
+      const int b = bx0 + round * cus + cu;
       ++round;
-      if (tile_index >= tx1) break;   // the last round may be partial
+      if (b >= bx1) continue;   // the last round may be partial (the stream, if any, still follows)
+      tc = big_tile_at(offsets, n_exp, n_tiles, small_rows, b);
     } else {
       tl = static_cast<int>(u / KT);
       kb = static_cast<int>(u - static_cast<int64_t>(tl) * KT);
       ke = static_cast<int>(min(static_cast<int64_t>(KT), kb + (u_end - u)));
-      tile_index = ts0 + tl;
       u += ke - kb;
+      tc = tl < stream_big ? big_tile_at(offsets, n_exp, n_tiles, small_rows, bx0 + tl)
+                           : small_tile_at(offsets, n_exp, n_tiles, small_rows, sx0 + tl - stream_big);
     }
     const int last = ke - 1;
-    const Tile tc = tile_at(offsets, n_exp, n_tiles, tile_index);
     const int cols = min(BN, Nout - tc.col0);
     gbase = reinterpret_cast<const unsigned char*>(
         is_b ? B + (static_cast<size_t>(tc.expert) * Nout + tc.col0) * K
@@ -339,16 +395,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     // there (their first segment, which they finished long ago).
     const bool partial_only = kb > 0;
     f32x4* my_slot = reinterpret_cast<f32x4*>(slots + static_cast<size_t>(blockIdx.x) * kSlotFloats) + tid_l;
-    int c2_end = cu + 1;
+    int n_contrib = 0;
     if (!partial_only && ke < KT) {
-      while (c2_end < cus && share_begin(c2_end) < static_cast<int64_t>(tl + 1) * KT) ++c2_end;
       if (tid == 0) {
-        // One thread polls (relaxed loads that go to L2, no cache maintenance inside the loop).
-        for (int c2 = cu + 1; c2 < c2_end; ++c2) {
-          if (share_begin(c2 + 1) == share_begin(c2)) continue;   // a CU with an empty share sends nothing
-          const uint32_t* flag = flags + ((c2 << 3) | xcd);
+        // One thread lists the CUs after this one whose share begins inside this tile (skipping empty
+        // shares) and polls their flags (relaxed loads that go to L2, no cache maintenance in the loop).
+        int n = 0;
+        for (int c2 = cu + 1; c2 < cus && share_begin(c2) < static_cast<int64_t>(tl + 1) * KT; ++c2) {
+          if (share_begin(c2 + 1) == share_begin(c2)) continue;
+          const int b2 = (c2 << 3) | xcd;
+          contrib[++n] = b2;
           int spins = 0;
-          while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+          while (__hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
             if (++spins >= kSpinLimit) {
               flags[gridDim.x] = 1u;   // reported to the host; the result of this tile is incomplete
               break;
@@ -356,9 +414,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
             __builtin_amdgcn_s_sleep(16);
           }
         }
+        contrib[0] = n;
       }
       __syncthreads();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // once per thread, after the flags are up
+      n_contrib = contrib[0];
     }
 
     // ---- epilogue --------------------------------------------------------------------------------
@@ -379,16 +439,32 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[q][e] = read_acc(acc[mi][ni][q * 4 + e]);
+        // Blocks of 32 rows with no valid row are neither sent nor fetched (a 3-row tail tile moves an
+        // eighth of a slot).
+        const bool live = wm * 128 + mi * 32 < tc.rows;
         if (partial_only) {
+          if (live) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) my_slot[((mi * 4 + ni) * 4 + q) * kThreads] = v[q];
+            for (int q = 0; q < 4; ++q) my_slot[((mi * 4 + ni) * 4 + q) * kThreads] = v[q];
+          }
         } else {
-          for (int c2 = cu + 1; c2 < c2_end; ++c2) {   // partial sums, in CU order (fixed summation order)
-            if (share_begin(c2 + 1) == share_begin(c2)) continue;
-            const f32x4* slot =
-                reinterpret_cast<const f32x4*>(slots + static_cast<size_t>((c2 << 3) | xcd) * kSlotFloats) + tid_l;
+          // Partial sums are added in CU order (fixed summation order); the loads of 8 CUs' slots
+          // go out together, so the wait is one memory latency per 8 CUs, not per CU.
+          for (int c0 = 0; live && c0 < n_contrib; c0 += 8) {
+            f32x4 p[8][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] += slot[((mi * 4 + ni) * 4 + q) * kThreads];
+            for (int j = 0; j < 8; ++j) {
+              const bool has = c0 + j < n_contrib;
+              const int b2 = contrib[1 + min(c0 + j, n_contrib - 1)];
+              const f32x4* slot = reinterpret_cast<const f32x4*>(slots + static_cast<size_t>(b2) * kSlotFloats) + tid_l;
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                p[j][q] = has ? slot[((mi * 4 + ni) * 4 + q) * kThreads] : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] += p[j][q];
           }
           const int r = mi * 32 + frow;
 #pragma unroll
@@ -419,14 +495,13 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       continue;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (c2_end > cu + 1) {
+    if (n_contrib > 0) {
       // every thread has read the partial sums: lower the flags (the scratch may be reused by a
       // replay of the same launch, whose flags carry the same value)
       __syncthreads();
       if (tid == 0)
-        for (int c2 = cu + 1; c2 < c2_end; ++c2)
-          if (share_begin(c2 + 1) != share_begin(c2))
-            __hip_atomic_store(flags + ((c2 << 3) | xcd), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 1; i <= n_contrib; ++i)
+          __hip_atomic_store(flags + contrib[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // Read back 16 bytes per lane: an instruction covers 4 rows x 256 bytes.
     const int er = (tid_l & 63) >> 4, ec = tid_l & 15;

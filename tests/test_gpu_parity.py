@@ -185,6 +185,8 @@ def ragged_offsets(counts):
     ("bf16", 192, 520, [300, 0, 513, 1, 255, 256]),
     ("bf16", 200, 264, [257, 31]),
     ("bf16", 512, 1024, [1024, 1000, 0, 24]),
+    ("bf16", 4096, 256, [300, 3, 0, 257]),        # long K: tail tiles go through the cut k-tile stream
+    ("bf16", 256, 4096, [129, 128, 600]),         # long K in the second GEMM
     ("f32", 64, 136, [70, 0, 64, 1]),
     ("f32", 256, 1024, [64, 64, 64, 64]),
 ])
