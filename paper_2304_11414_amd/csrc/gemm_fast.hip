@@ -65,6 +65,28 @@ __device__ __forceinline__ float read_acc(float a) {
   return v;
 }
 
+// Four at a time, stage by stage: the four dependency chains (mul, fma, mul, exp2, add, rcp, mul)
+// interleave, so the latency of each instruction is hidden by the other three elements.
+__device__ __forceinline__ f32x4 gelu_tanh4(f32x4 u) {
+  // (the sched_barriers keep the compiler from folding the stages back into four serial chains)
+  f32x4 z, e, r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) z[i] = fmaf(0.044715f * u[i], u[i], 1.0f);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) z[i] = (-2.302208198f * u[i]) * z[i];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) e[i] = __builtin_amdgcn_exp2f(z[i]);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) e[i] = 1.0f + e[i];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_rcpf(e[i]);
+  __builtin_amdgcn_sched_barrier(0);
+  return u * r;
+}
+
 template <int OFF>
 __device__ __forceinline__ void lds_read16(bf16x8& dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
@@ -470,12 +492,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             f32x4 w = v[q];
-            if (GELU) {
-              w[0] = gelu_tanh(w[0]);
-              w[1] = gelu_tanh(w[1]);
-              w[2] = gelu_tanh(w[2]);
-              w[3] = gelu_tanh(w[3]);
-            }
+            if (GELU) w = gelu_tanh4(w);
             const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
             const uint32_t a = epi_l + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
             const uint32_t lo = pack_bf16x2(w[0], w[1]), hi = pack_bf16x2(w[2], w[3]);
@@ -507,14 +524,24 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const int er = (tid_l & 63) >> 4, ec = tid_l & 15;
     const int ncol = cols - wn * 128;   // valid columns of this wavefront's half (may be <= 0)
     bf16_t* cbase = C + static_cast<size_t>(tc.row0 + wm * 128) * Nout + tc.col0 + wn * 128 + ec * 8;
-#pragma unroll 2
-    for (int i = 0; i < 32; ++i) {
-      const int r = i * 4 + er;
-      u32x4 v;
-      const uint32_t a = epi_l + r * 256 + ((ec ^ (r & 15)) << 4);
-      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
-      if (wm * 128 + r < tc.rows && ec * 8 < ncol)
-        *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v;
+    for (int i0 = 0; i0 < 32; i0 += 8) {   // 8 reads in flight, then their 8 stores
+      u32x4 v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = (i0 + j) * 4 + er;
+        const uint32_t a = epi_l + r * 256 + ((ec ^ (r & 15)) << 4);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(v[j]) : "v"(a) : "memory");
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
+                   :
+                   : "memory");
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = (i0 + j) * 4 + er;
+        if (wm * 128 + r < tc.rows && ec * 8 < ncol)
+          *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v[j];
+      }
     }
   }
 #undef PPMOE_STEP
