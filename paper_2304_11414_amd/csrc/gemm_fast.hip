@@ -21,18 +21,23 @@
 // cycle (16 consecutive rows, same logical piece) from 64 banks, and with this swizzle they touch 16
 // different 16-byte slots; so do the 16 lanes (2 rows x 8 pieces) of a ds_write_b128.
 //
-// Scheduling: the kernel is persistent (one block per CU).  The tile list (expert-major, then n-tile,
-// then m-tile) is cut into 8 contiguous runs of whole tiles, one per XCD (consecutive block ids go
-// round-robin over the XCDs), so the CUs sharing an L2 work on the same weight panels; inside an
-// XCD the run is treated as one stream of k-tiles and cut into equal shares, one per CU (stream-K):
-// no CU idles because the tile count is not a multiple of the CU count.  A tile cut between CUs is
-// finished by the CU that holds its first k-tile (the last thing that CU does); the others wrote
-// their partial accumulators to a scratch slot as the first thing they did and raised a flag.
+// Scheduling: the kernel is persistent (one block per CU; consecutive block ids go round-robin over
+// the 8 XCDs, checked once per process with the XCC_ID register).  Row tiles are "big" (up to 256
+// rows) or, for the last at most 128 rows of an expert, "small" (computed as 32/64/128 rows x 256
+// columns with the four wavefronts side by side: a tail of a few rows costs a few MFMAs, not a tile).
+// Each XCD owns a contiguous eighth of the big-tile list and of the small-tile list, so the CUs
+// sharing an L2 work on the same panels.  Its CUs take the big tiles whole, in rounds; what is left
+// (big tiles when there are fewer than CUs, and the small tiles) is one stream of k-tiles cut into
+// shares (stream-K).  A tile cut between CUs is finished by the CU that holds its first k-tile; the
+// others store their partial accumulators to a scratch slot and raise a flag.  Writer and reader of
+// a slot sit on the same XCD, so the hand-over goes through their shared L2 without device-scope
+// cache maintenance (the device-scope fences are kept as a fallback for any other placement).
 //
 // All LDS traffic is inline assembly with hand-counted lgkmcnt waits, so that the MFMA stream never
 // waits for more than it needs; global loads are plain loads (the compiler counts vmcnt for them).
 
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 
@@ -103,14 +108,24 @@ struct Tile {
   int expert, row0, rows, col0;
 };
 
+// How a tile is computed.  0: "big", the wavefronts form a 2 x 2 grid of 128 x 128 sub-tiles.
+// 1, 2, 4: "small", at most 32, 64, 128 rows: the wavefronts stand side by side, each owning all
+// the rows and 64 of the 256 columns (KIND x 2 accumulator blocks instead of 4 x 4), so a tail of a
+// few rows costs its share of MFMAs and the fetch of its weight panel, not a whole tile.
+__device__ __forceinline__ int tile_kind(int rows, bool small) {
+  return !small ? 0 : rows <= 32 ? 1 : rows <= 64 ? 2 : 4;
+}
+
 // An expert's rows are cut into m-tiles of BM; its last m-tile is "small" when it has at most
 // kSmallRows rows.  The tile list has two parts: all the other ("big") tiles, ordered expert-major,
 // then n-tile, then m-tile (m fastest); then the small tiles, ordered expert-major, then n-tile.
 // (Only when K is long: with a short K loop the hand-over of partial sums costs more than letting
 // the tail tile take a slot of a round; measured on K = 2048 against K = 8192.)
 constexpr int kSmallRows = 128;
-constexpr int kSmallMinKTiles = 64;
-constexpr int kMinShare = 16;   // k-tiles: the smallest share of a cut stream a CU is given
+#ifndef PPMOE_MIN_SHARE
+#define PPMOE_MIN_SHARE 16
+#endif
+constexpr int kMinShare = PPMOE_MIN_SHARE;   // k-tiles: the smallest share of a cut stream a CU is given
 
 __device__ __forceinline__ void expert_tiles(int cnt, int small_rows, int& big_m, int& small) {
   const int m_tiles = (cnt + BM - 1) / BM;
@@ -180,13 +195,28 @@ __device__ __forceinline__ Tile small_tile_at(const int32_t* __restrict__ offset
 constexpr int kSlotFloats = BM * BN;
 constexpr int kSpinLimit = 1 << 17;   // polls of a flag (a few tenths of a second) before giving up
 
+// The XCD (accelerator complex die) this wavefront runs on.
+__device__ __forceinline__ uint32_t xcc_id() {
+  uint32_t v;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(v));
+  return v;
+}
+
+// Set-up check of the placement rule the hand-over of partial sums relies on (block b runs on XCD
+// b mod 8, so blocks b and b' with b = b' mod 8 share an L2): every block reports where it ran.
+__global__ __launch_bounds__(kThreads) void xcc_probe_kernel(uint32_t* __restrict__ out) {
+  if (threadIdx.x == 0) out[blockIdx.x] = xcc_id();
+}
+
 template <bool GELU>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
-    uint32_t* __restrict__ flags, uint32_t epoch) {
+    uint32_t* __restrict__ flags, uint32_t epoch, int same_l2) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
+  __shared__ int contrib_foreign;
+  const uint32_t my_xcc = xcc_id();
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -210,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   const int n_tiles = (Nout + BN - 1) / BN;
   const int KT = K / BK;
   int total_big, total_small;
-  const int small_rows = KT >= kSmallMinKTiles ? kSmallRows : 0;
+  const int small_rows = kSmallRows;
   count_tiles(offsets, n_exp, n_tiles, small_rows, total_big, total_small);
   const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3, cus = gridDim.x >> 3;
   const int bx0 = static_cast<int>(static_cast<int64_t>(total_big) * xcd / 8);
@@ -228,51 +258,34 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   int64_t u = share_begin(cu);
   const int64_t u_end = share_begin(cu + 1);
 
-  // ---- addresses that do not depend on the tile ----------------------------------------------------
   // Staging: a tile is 512 rows (256 token, 256 weight) of 128 bytes; one load instruction covers 8
   // rows, so a tile is 64 instructions, 16 per wavefront.  Wavefronts 0,1 fetch token rows, 2,3
   // weight rows; instruction n of a wavefront covers rows (wave & 1) * 128 + n * 8 .. + 8.
   const bool is_b = wave >= 2;
-  const int lrow = lane >> 3, piece = lane & 7;
-  // LDS write address: row*128 + swizzled piece; rows n*8 + lrow: (row >> 1) & 7 = (n & 1) * 4 + (lrow >> 1)
-  uint32_t wr_addr[2];
-#pragma unroll
-  for (int par = 0; par < 2; ++par) {
-    const int sw = (par * 4 + (lrow >> 1)) & 7;
-    wr_addr[par] = lds0 + (is_b ? kOperandBytes : 0) + ((wave & 1) * 128 + lrow) * 128 + ((piece ^ sw) << 4);
-  }
-  // MFMA operands: lane holds row (lane & 31) of a 32-row fragment and the 8 k-values of piece
-  // 2*ks + (lane >> 5).
-  const int frow = lane & 31, half = lane >> 5;
-  uint32_t tok_addr[4], wgt_addr[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const int slot = ((2 * ks + half) ^ ((frow >> 1) & 7)) << 4;
-    tok_addr[ks] = lds0 + (wm * 128 + frow) * 128 + slot;
-    wgt_addr[ks] = lds0 + kOperandBytes + (wn * 128 + frow) * 128 + slot;
-  }
-  const uint32_t epi = lds0 + wave * (128 * 256);   // this wavefront's 32 KiB for the output transpose
-
   const unsigned char* gbase;
   uint32_t goff[16];   // byte offset of this lane's piece in row n*8 + lrow (rows past the end re-read the last)
-  u32x4 stage[16];
-  auto gload = [&](int n, int t) {   // t: tile index along K
-    stage[n] = *reinterpret_cast<const u32x4*>(gbase + goff[n] + static_cast<size_t>(t) * (BK * 2));
-  };
   f32x16 acc[4][4];
-  bf16x8 f0[8], f1[8];
 
 // The sched_barrier pins the hand-written interleaving of MFMAs and memory operations: without it
 // the compiler sinks the fragment reads below the MFMAs (to reuse their registers) and the next
 // k-step then waits for LDS.
+// KIND (a constant of the enclosing segment body) selects the accumulator blocks and fragments in
+// use: all 4 x 4 for a big tile, KIND x 2 for a small one.
 #define PPMOE_MFMA(f, mi, ni)                                                                        \
   do {                                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
+    if (KIND == 0 || (mi < KIND && ni < 2))                                                          \
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[4 + ni], f[mi], acc[mi][ni], 0, 0, 0); \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
-#define PPMOE_READ_TOK(f, i, ks, buf) lds_read16<i * 4096>(f[i], tok_addr[ks] + (buf))
-#define PPMOE_READ_WGT(f, i, ks, buf) lds_read16<i * 4096>(f[4 + i], wgt_addr[ks] + (buf))
+#define PPMOE_READ_TOK(f, i, ks, buf)                                                  \
+  do {                                                                                 \
+    if (KIND == 0 || i < KIND) lds_read16<i * 4096>(f[i], tok_a[ks] + (buf));           \
+  } while (0)
+#define PPMOE_READ_WGT(f, i, ks, buf)                                                  \
+  do {                                                                                 \
+    if (KIND == 0 || i < 2) lds_read16<i * 4096>(f[4 + i], wgt_a[ks] + (buf));          \
+  } while (0)
 #define PPMOE_WRITE(n, buf) lds_write16<(n) * 1024>(wr_addr[(n) & 1] + (buf), stage[n])
 #define PPMOE_WRITE4(q, buf)     \
   do {                           \
@@ -312,19 +325,19 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     PPMOE_MFMA(cur, 3, 1);                                                                           \
     if (DO_STAGE) PPMOE_WRITE(4 * Q + 3, WB);                                                        \
     PPMOE_MFMA(cur, 2, 2);                                                                           \
-    if (DO_STAGE) gload(4 * Q + 0, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 0, LT);                                                              \
     PPMOE_MFMA(cur, 2, 3);                                                                           \
-    if (DO_STAGE) gload(4 * Q + 1, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 1, LT);                                                              \
     PPMOE_MFMA(cur, 3, 2);                                                                           \
-    if (DO_STAGE) gload(4 * Q + 2, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 2, LT);                                                              \
     PPMOE_MFMA(cur, 3, 3);                                                                           \
-    if (DO_STAGE) gload(4 * Q + 3, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 3, LT);                                                              \
   } while (0)
 
 
   while (round < rounds || u < u_end) {
     // ---- one segment: k-tiles [kb, ke) of one output tile ---------------------------------------
-    int tl = 0, kb = 0, ke = KT;
+    int tl = 0, kb = 0, ke = KT, kind = 0;
     Tile tc;
     if (round < rounds) {
       const int b = bx0 + round * cus + cu;
@@ -338,7 +351,33 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       u += ke - kb;
       tc = tl < stream_big ? big_tile_at(offsets, n_exp, n_tiles, small_rows, bx0 + tl)
                            : small_tile_at(offsets, n_exp, n_tiles, small_rows, sx0 + tl - stream_big);
+      kind = tile_kind(tc.rows, tl >= stream_big);
     }
+    // Per-lane addresses.  They do not depend on the tile, but they are derived here, per segment,
+    // from an opaque copy of the lane id: computed once before the segment loop they would all stay
+    // live across it (some forty registers, which then spill).
+    int lane_s = lane;
+    asm volatile("" : "+v"(lane_s));
+    const int lrow = lane_s >> 3, piece = lane_s & 7;
+    // LDS write address: row*128 + swizzled piece; rows n*8 + lrow: (row >> 1) & 7 = (n & 1) * 4 + (lrow >> 1)
+    uint32_t wr_addr[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int sw = (par * 4 + (lrow >> 1)) & 7;
+      wr_addr[par] = lds0 + (is_b ? kOperandBytes : 0) + ((wave & 1) * 128 + lrow) * 128 + ((piece ^ sw) << 4);
+    }
+    // MFMA operands: lane holds row (lane_s & 31) of a 32-row fragment and the 8 k-values of piece
+    // 2*ks + (lane_s >> 5).
+    const int frow = lane_s & 31, half = lane_s >> 5;
+    uint32_t tok_addr[4], wgt_addr[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int slot = ((2 * ks + half) ^ ((frow >> 1) & 7)) << 4;
+      tok_addr[ks] = lds0 + (wm * 128 + frow) * 128 + slot;
+      wgt_addr[ks] = lds0 + kOperandBytes + (wn * 128 + frow) * 128 + slot;
+    }
+    const uint32_t epi = lds0 + wave * (128 * 256);   // this wavefront's 32 KiB for the output transpose
+
     const int last = ke - 1;
     const int cols = min(BN, Nout - tc.col0);
     gbase = reinterpret_cast<const unsigned char*>(
@@ -357,59 +396,102 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    // ---- prologue --------------------------------------------------------------------------------
-    // The first tile goes through the registers into buffer 0; then the second is loaded, its first
-    // quarter written to buffer 1 and replaced by the first quarter of the third: the state every
-    // loop iteration starts in.  Tiles past the end of the segment are loaded from its last tile
-    // instead (never used), which keeps the loop free of branches.
+    // The K loop of one segment, compiled once per tile kind.
+    auto run_segment = [&](auto kind_c) __attribute__((always_inline)) {
+      constexpr int KIND = decltype(kind_c)::value;
+      // Staging registers and fragments belong to the segment: declared outside they would carry
+      // their last values across the epilogue wherever a kind leaves some of them unwritten.
+      u32x4 stage[16];
+      auto gload = [&](int n, int t) {   // t: tile index along K
+        stage[n] = *reinterpret_cast<const u32x4*>(gbase + goff[n] + static_cast<size_t>(t) * (BK * 2));
+      };
+      bf16x8 f0[8], f1[8];
+      // Small tile: every wavefront reads the token rows from row 0 and its own 64 weight rows.
+      // (the shifts are made opaque so that the shifted addresses are computed here, per segment, and
+      // not once per kind before the segment loop, where they would be live across everything)
+      uint32_t tok_a[4], wgt_a[4];
+      uint32_t tok_shift = KIND ? wm * (128 * 128) : 0, wgt_shift = KIND ? (wave * 64 - wn * 128) * 128 : 0;
+      asm volatile("" : "+s"(tok_shift), "+s"(wgt_shift));
 #pragma unroll
-    for (int n = 0; n < 16; ++n) gload(n, kb);
-    __builtin_amdgcn_s_barrier();   // the previous segment's output transpose is out of LDS
-    PPMOE_WRITE4(0, 0); PPMOE_WRITE4(1, 0); PPMOE_WRITE4(2, 0); PPMOE_WRITE4(3, 0);
-#pragma unroll
-    for (int n = 0; n < 16; ++n) gload(n, min(kb + 1, last));
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    PPMOE_READ_TOK(f0, 0, 0, 0); PPMOE_READ_WGT(f0, 0, 0, 0);
-    PPMOE_READ_TOK(f0, 1, 0, 0); PPMOE_READ_WGT(f0, 1, 0, 0);
-    PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
-    PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
-    // (after the reads, so that the loop's first wait sees the same 8 reads + 4 writes as every other)
-    PPMOE_WRITE4(0, kBufBytes);
-#pragma unroll
-    for (int n = 0; n < 4; ++n) gload(n, min(kb + 2, last));
+      for (int ks = 0; ks < 4; ++ks) {
+        tok_a[ks] = tok_addr[ks] - tok_shift;
+        wgt_a[ks] = wgt_addr[ks] + wgt_shift;
+      }
+      // Token rows are staged 32 at a time by wavefront 0 (quarter q of its loads = rows 32q..32q+31):
+      // a small tile only fetches the row blocks it has (wavefront 1 stages rows 128..255: none).
+      auto stage_live = [&](int q) -> bool { return KIND == 0 || is_b || (wave == 0 && q < KIND); };
 
-    // ---- main loop -------------------------------------------------------------------------------
-    // At the top of tile t (i = t - kb): buffer i&1 holds tile t (visible to all), f0 <- its k-step 0
-    // (in flight), stage[4..15] hold quarters 1..3 of tile t+1 and stage[0..3] quarter 0 of tile t+2
-    // (in flight), quarter 0 of tile t+1 is already in buffer (i+1)&1.
-    for (int t = kb; t < ke; ++t) {
-      const uint32_t rb = ((t - kb) & 1) * kBufBytes, wb = kBufBytes - rb;
-      const int lt = min(t + 2, last);
-      // LDS operations complete in order: the 8 reads being waited for were always followed by
-      // exactly 4 writes, so "at most 4 outstanding" means the reads have landed.
-      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
-      PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
-      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f1)::"memory");
-      PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
-      asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
-      PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
-      // Every read of tile t and every write of tile t+1 by this wavefront has completed once
-      // lgkmcnt is 0; after the barrier that holds for the whole block.
-      asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");
+      // ---- prologue ------------------------------------------------------------------------------
+      // The first tile goes through the registers into buffer 0; then the second is loaded, its first
+      // quarter written to buffer 1 and replaced by the first quarter of the third: the state every
+      // loop iteration starts in.  Tiles past the end of the segment are loaded from its last tile
+      // instead (never used), which keeps the loop free of branches.
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (stage_live(q)) {
+#pragma unroll
+          for (int n = 4 * q; n < 4 * q + 4; ++n) gload(n, kb);
+        }
+      __builtin_amdgcn_s_barrier();   // the previous segment's output transpose is out of LDS
+      PPMOE_WRITE4(0, 0); PPMOE_WRITE4(1, 0); PPMOE_WRITE4(2, 0); PPMOE_WRITE4(3, 0);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (stage_live(q)) {
+#pragma unroll
+          for (int n = 4 * q; n < 4 * q + 4; ++n) gload(n, min(kb + 1, last));
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
-      // k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t
-      // is leaving, and is replaced in the registers by quarter 0 of tile t+3.
-      const int lt3 = min(t + 3, last);
-      PPMOE_STEP(f1, f0, 0, wb, 0, rb, lt3, true, true);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f0)::"memory");
+      PPMOE_READ_TOK(f0, 0, 0, 0); PPMOE_READ_WGT(f0, 0, 0, 0);
+      PPMOE_READ_TOK(f0, 1, 0, 0); PPMOE_READ_WGT(f0, 1, 0, 0);
+      PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
+      PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
+      // (after the reads, so that the loop's first wait sees the same reads + 4 writes as every other)
+      PPMOE_WRITE4(0, kBufBytes);
+      if (stage_live(0)) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) gload(n, min(kb + 2, last));
+      }
+
+      // ---- main loop -----------------------------------------------------------------------------
+      // At the top of tile t (i = t - kb): buffer i&1 holds tile t (visible to all), f0 <- its k-step
+      // 0 (in flight), stage[4..15] hold quarters 1..3 of tile t+1 and stage[0..3] quarter 0 of tile
+      // t+2 (in flight), quarter 0 of tile t+1 is already in buffer (i+1)&1.
+      for (int t = kb; t < ke; ++t) {
+        const uint32_t rb = ((t - kb) & 1) * kBufBytes, wb = kBufBytes - rb;
+        const int lt = min(t + 2, last);
+        // LDS operations complete in order: the reads being waited for were always followed by
+        // exactly 4 writes, so "at most 4 outstanding" means the reads have landed.
+        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+        PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
+        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f1)::"memory");
+        PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
+        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+        PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
+        // Every read of tile t and every write of tile t+1 by this wavefront has completed once
+        // lgkmcnt is 0; after the barrier that holds for the whole block.
+        asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");
+        __builtin_amdgcn_s_barrier();
+        // k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t
+        // is leaving, and is replaced in the registers by quarter 0 of tile t+3.
+        const int lt3 = min(t + 3, last);
+        PPMOE_STEP(f1, f0, 0, wb, 0, rb, lt3, true, true);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f0)::"memory");
+    };
+    if (kind == 0) run_segment(std::integral_constant<int, 0>{});
+    else if (kind == 1) run_segment(std::integral_constant<int, 1>{});
+    else if (kind == 2) run_segment(std::integral_constant<int, 2>{});
+    else run_segment(std::integral_constant<int, 4>{});
 
     // Per-segment opaque copies: they stop the compiler from hoisting the address arithmetic of the
     // code below out of the segment loop, where it would cost a few hundred live registers.
     uint32_t epi_l = epi;
     int tid_l = tid;
     asm volatile("" : "+v"(epi_l), "+v"(tid_l));
+    // Where this wavefront's accumulator blocks sit in the tile (see tile_kind).
+    const int row_base = kind ? 0 : wm * 128, col_base = kind ? wave * 64 : wn * 128;
+    const int ni_lim = kind ? 2 : 4, wave_cols = kind ? 64 : 128;
 
     // A segment that does not hold the first k-tile of its output tile hands its partial sums to the
     // CU that does (through this block's scratch slot); the one that holds it writes the output
@@ -422,24 +504,37 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       if (tid == 0) {
         // One thread lists the CUs after this one whose share begins inside this tile (skipping empty
         // shares) and polls their flags (relaxed loads that go to L2, no cache maintenance in the loop).
-        int n = 0;
+        int n = 0, foreign = 0;
         for (int c2 = cu + 1; c2 < cus && share_begin(c2) < static_cast<int64_t>(tl + 1) * KT; ++c2) {
           if (share_begin(c2 + 1) == share_begin(c2)) continue;
           const int b2 = (c2 << 3) | xcd;
           contrib[++n] = b2;
           int spins = 0;
-          while (__hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+          uint32_t f;
+          while (((f = __hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 4) != epoch) {
             if (++spins >= kSpinLimit) {
-              flags[gridDim.x] = 1u;   // reported to the host; the result of this tile is incomplete
+              flags[gridDim.x] = 1u;   // left for a debugger: the result of this tile is incomplete
               break;
             }
             __builtin_amdgcn_s_sleep(16);
           }
+          if ((f & 15u) != my_xcc) {   // the partial sums sit in another XCD's L2: the set-up check was wrong
+            foreign = 1;
+            flags[gridDim.x] = 2u;
+          }
         }
         contrib[0] = n;
+        contrib_foreign = foreign;
       }
       __syncthreads();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // once per thread, after the flags are up
+      // Once per thread, after the flags are up.  Within an XCD the partial sums are in the shared L2
+      // (stores write through the L1, and this CU has never read these lines since its L1 was
+      // invalidated at the start of the kernel), so ordering against the barrier is all it takes;
+      // the device-scope acquire invalidates the L2, which then misses on every panel being streamed.
+      if (same_l2 && !contrib_foreign)
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      else
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       n_contrib = contrib[0];
     }
 
@@ -463,7 +558,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
           for (int e = 0; e < 4; ++e) v[q][e] = read_acc(acc[mi][ni][q * 4 + e]);
         // Blocks of 32 rows with no valid row are neither sent nor fetched (a 3-row tail tile moves an
         // eighth of a slot).
-        const bool live = wm * 128 + mi * 32 < tc.rows;
+        const bool live = row_base + mi * 32 < tc.rows && ni < ni_lim;
         if (partial_only) {
           if (live) {
 #pragma unroll
@@ -490,7 +585,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
           }
           const int r = mi * 32 + frow;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; live && q < 4; ++q) {
             f32x4 w = v[q];
             if (GELU) w = gelu_tanh4(w);
             const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
@@ -505,10 +600,17 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     if (partial_only) {
       // Release: every thread makes its own stores visible device-wide, then the block meets, then
       // one thread raises the flag (a relaxed store is enough after the fences).
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      // (Within an XCD: the stores have reached the shared L2 once vmcnt is 0.  The device-scope
+      // release would write back every dirty line of the L2 -- the output tiles -- once per hand-over.)
+      if (same_l2) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      }
       __syncthreads();
       if (tid == 0)
-        __hip_atomic_store(flags + blockIdx.x, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(flags + blockIdx.x, (epoch << 4) | my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       continue;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -522,9 +624,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     }
     // Read back 16 bytes per lane: an instruction covers 4 rows x 256 bytes.
     const int er = (tid_l & 63) >> 4, ec = tid_l & 15;
-    const int ncol = cols - wn * 128;   // valid columns of this wavefront's half (may be <= 0)
-    bf16_t* cbase = C + static_cast<size_t>(tc.row0 + wm * 128) * Nout + tc.col0 + wn * 128 + ec * 8;
-    for (int i0 = 0; i0 < 32; i0 += 8) {   // 8 reads in flight, then their 8 stores
+    const int ncol = min(cols - col_base, wave_cols);   // valid columns of this wavefront's part (may be <= 0)
+    const int nrow = tc.rows - row_base;                // valid rows of it (may be <= 0)
+    bf16_t* cbase = C + static_cast<size_t>(tc.row0 + row_base) * Nout + tc.col0 + col_base + ec * 8;
+    for (int i0 = 0; i0 < 32 && i0 * 4 < nrow; i0 += 8) {   // 8 reads in flight, then their 8 stores
       u32x4 v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -539,7 +642,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int r = (i0 + j) * 4 + er;
-        if (wm * 128 + r < tc.rows && ec * 8 < ncol)
+        if (r < nrow && ec * 8 < ncol)
           *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v[j];
       }
     }
@@ -555,8 +658,9 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 }  // namespace fast
 
 size_t grouped_gemm_fast_workspace_bytes() {
+  // slots, flags (+1 word), one word per block for the placement check
   return static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats * sizeof(float) +
-         (kMaxPersistentBlocks + 1) * sizeof(uint32_t) + 256;
+         (2 * kMaxPersistentBlocks + 1) * sizeof(uint32_t) + 256;
 }
 
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
@@ -587,17 +691,31 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
   }();
   if (setup.err != hipSuccess) return setup.err;
   static std::atomic<uint32_t> launches{0};
-  uint32_t epoch = ++launches;
-  if (epoch == 0) epoch = ++launches;   // 0 means "flag down"
+  uint32_t epoch = ++launches & 0x0fffffffu;   // 28 bits: the flag word also carries the XCD id
+  if (epoch == 0) epoch = ++launches & 0x0fffffffu;   // 0 means "flag down"
   float* slots = static_cast<float*>(workspace);
   uint32_t* flags = reinterpret_cast<uint32_t*>(slots + static_cast<size_t>(kMaxPersistentBlocks) * kSlotFloats);
   (void)max_rows;
+
+  // First launch of the process (it synchronises the stream, once): do blocks b and b + 8 share an
+  // XCD, as the cheap hand-over assumes?  If not, every hand-over uses device-scope fences.
+  static const int same_l2 = [&]() -> int {
+    uint32_t* where = flags + kMaxPersistentBlocks + 1;
+    uint32_t host[kMaxPersistentBlocks];
+    xcc_probe_kernel<<<setup.blocks, kThreads, 0, s>>>(where);
+    if (hipMemcpyAsync(host, where, setup.blocks * sizeof(uint32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      return 0;
+    for (int b = 8; b < setup.blocks; ++b)
+      if (host[b] != host[b & 7]) return 0;
+    return 1;
+  }();
   if (gelu)
     grouped_gemm_bf16_fast_kernel<true><<<setup.blocks, kThreads, kLdsBytes, s>>>(
-        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch);
+        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2);
   else
     grouped_gemm_bf16_fast_kernel<false><<<setup.blocks, kThreads, kLdsBytes, s>>>(
-        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch);
+        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2);
   return hipGetLastError();
 }
 
