@@ -150,6 +150,34 @@ def main():
         for h in e:
             B.moe_event_destroy(h)
 
+    # Empirical ceilings of this device, measured here with the library's own helpers: a plain
+    # copy kernel (HBM) and a register-resident MFMA loop with the GEMM's launch shape (matrix
+    # cores; random operands draw more power and settle at a lower clock than constant ones).
+    def timed(fn, reps):
+        fn()
+        e0, e1 = B.moe_event_create(), B.moe_event_create()
+        torch.cuda.synchronize()
+        B.moe_event_record(e0)
+        for _ in range(reps):
+            fn()
+        B.moe_event_record(e1)
+        torch.cuda.synchronize()
+        ms = B.moe_event_elapsed_ms(e0, e1) / reps
+        B.moe_event_destroy(e0)
+        B.moe_event_destroy(e1)
+        return ms
+    ceilings = {}
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    ceilings["copy_gbs"] = round(2 * src.numel() / (timed(lambda: B.moe_copy_bytes(src, dst), 10) * 1e-3) / 1e9, 1)
+    del src, dst
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    for name, rnd in (("mfma_random_tflops", 1), ("mfma_constant_tflops", 0)):
+        fl = []
+        ms = timed(lambda: fl.append(B.moe_mfma_probe(100000, rnd, sink)), 3)
+        ceilings[name] = round(fl[-1] / (ms * 1e-3) / 1e12, 1)
+
     views = B.workspace_views(cfg, ws)
     counts = views["counts"].cpu().numpy()
     A = int(views["offsets"][-1].item())
@@ -175,6 +203,9 @@ def main():
         "ffn_up_tflops": round(tflops_up, 2), "ffn_down_tflops": round(tflops_dn, 2),
         "ffn_frac_of_mfma_peak": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
                                        / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "empirical_ceilings": ceilings,
+        "ffn_frac_of_mfma_random_ceiling": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
+                                                 / 1e12 / ceilings["mfma_random_tflops"], 4),
         "gate_gbs": round(bytes_gate / (st["gate"] * 1e-3) / 1e9, 1),
         "slice_gbs": round(bytes_slice / (st["slice"] * 1e-3) / 1e9, 1),
         "combine_gbs": round(bytes_combine / (st["combine"] * 1e-3) / 1e9, 1),

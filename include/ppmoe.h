@@ -179,6 +179,15 @@ int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout);
  * which hardware byte counters (FETCH_SIZE, WRITE_SIZE) are calibrated when profiling. */
 int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Register-resident bf16 MFMA loop with the grouped GEMM's launch shape (one block of four
+ * wavefronts per CU, 16 accumulator blocks of 32x32x16 per wavefront) and no memory traffic: the
+ * empirical ceiling of the matrix cores, against which the GEMMs' TFLOP/s can be read next to the
+ * published peak.  Not part of the layer.  `iters` loop iterations of 16 MFMAs per wavefront;
+ * `random_operands` != 0 fills the operand registers with pseudo-random values in [-1, 1) (the
+ * clock then settles lower, under the power limit, than with constant operands); `sink`: device
+ * memory for 65536 floats (overwritten); `*flops` (host) receives the flop count of the launch. */
+int moe_mfma_probe(int64_t iters, int random_operands, float* sink, double* flops, void* stream);
+
 /* Timing helpers: thin wrappers over hipEvent so a caller without HIP headers can time stages.
  * moe_event_elapsed_ms synchronises on `stop` before reading. */
 int moe_event_create(void** event);

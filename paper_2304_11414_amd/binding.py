@@ -6,7 +6,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libppmoe.so")
@@ -47,6 +47,7 @@ _PROTOTYPES = {
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
     "moe_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
+    "moe_mfma_probe": (c_int, [c_int64, c_int, c_void_p, POINTER(c_double), c_void_p]),
     "moe_event_create": (c_int, [POINTER(c_void_p)]),
     "moe_event_destroy": (c_int, [c_void_p]),
     "moe_event_record": (c_int, [c_void_p, c_void_p]),
@@ -184,6 +185,14 @@ def moe_layer_forward(cfg, x, Wg, bias, W1, W2, out, workspace, stage_events=Non
 def moe_copy_bytes(src, dst, stream=None):
     _check(load_library().moe_copy_bytes(_ptr(src), _ptr(dst), _nbytes(src), _stream(stream)),
            "moe_copy_bytes")
+
+
+def moe_mfma_probe(iters, random_operands, sink, stream=None) -> float:
+    """Launches the probe; returns the flop count of the launch."""
+    fl = c_double()
+    _check(load_library().moe_mfma_probe(int(iters), int(bool(random_operands)), _ptr(sink), byref(fl),
+                                         _stream(stream)), "moe_mfma_probe")
+    return fl.value
 
 
 def moe_event_create() -> int:

@@ -296,6 +296,17 @@ int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {
                                       static_cast<hipStream_t>(stream)));
 }
 
+int moe_mfma_probe(int64_t iters, int random_operands, float* sink, double* flops, void* stream) {
+  if (sink == nullptr || flops == nullptr) return MOE_ERR_NULL;
+  if (iters < 0) return MOE_ERR_SHAPE;
+  int blocks = 0;
+  const hipError_t e = launch_mfma_probe(iters, random_operands, sink, &blocks,
+                                         static_cast<hipStream_t>(stream));
+  // per block: 4 wavefronts x 16 MFMAs of 2*32*32*16 flop per iteration
+  *flops = static_cast<double>(blocks) * 4.0 * 16.0 * 32768.0 * static_cast<double>(iters);
+  return hip_status(e);
+}
+
 int moe_event_create(void** event) {
   if (event == nullptr) return MOE_ERR_NULL;
   hipEvent_t ev;

@@ -55,6 +55,9 @@ hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32
                           const float* gate_w, void* out, hipStream_t s);
 
 hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t s);
+// Register-resident MFMA loop on one block per CU (at most kMaxPersistentBlocks); sink: one float per thread.
+hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, int* blocks_out,
+                             hipStream_t s);
 
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
 // workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).

@@ -76,7 +76,8 @@ hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStrea
   const int64_t pieces = bytes / 16;
   if (pieces == 0) return hipSuccess;
   int64_t want = (pieces + kCopyThreads - 1) / kCopyThreads;
-  int blocks = static_cast<int>(want < 256 * 16 ? want : 256 * 16);
+  // four blocks per CU: the fastest of the grid sizes and unroll factors tried on a 1 GiB copy
+  int blocks = static_cast<int>(want < 256 * 4 ? want : 256 * 4);
   copy_bytes_kernel<<<blocks, kCopyThreads, 0, s>>>(static_cast<const u32x4*>(src),
                                                     static_cast<u32x4*>(dst), pieces);
   return hipGetLastError();
