@@ -402,8 +402,13 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       // Staging registers and fragments belong to the segment: declared outside they would carry
       // their last values across the epilogue wherever a kind leaves some of them unwritten.
       u32x4 stage[16];
+      // Buffer loads: a scalar descriptor of the tile's panel (base = its first row), this lane's
+      // 32-bit byte offset in a register and the k-tile offset as a scalar -- one address register
+      // per lane and no 64-bit vector add per load.
+      const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<unsigned char*>(gbase), 0, 0x7fffffff, 0x00020000);
       auto gload = [&](int n, int t) {   // t: tile index along K
-        stage[n] = *reinterpret_cast<const u32x4*>(gbase + goff[n] + static_cast<size_t>(t) * (BK * 2));
+        stage[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[n], t * (BK * 2), 0);
       };
       bf16x8 f0[8], f1[8];
       // Small tile: every wavefront reads the token rows from row 0 and its own 64 weight rows.
