@@ -298,6 +298,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   // One k-step: 16 MFMAs on `cur`, the 8 fragment reads of the next k-step into `nxt`, and one
   // quarter (4 instructions) of the staging traffic: write quarter Q to LDS, then reload it.
   // RB/WB: byte offsets of the buffer read from / written to.  NKS: k-step the reads are for.
+  // One memory instruction per MFMA, and never two LDS writes in consecutive slots: four wavefronts
+  // writing 1 KiB each in the same 32 cycles exceed what the LDS takes in, and the wavefront then
+  // stalls at the next write (measured: 4 writes in 4 consecutive slots cost 56 cycles per k-step,
+  // the same 4 writes one every 4 slots cost nothing).  The last LDS instruction of a k-step is a
+  // write and every read precedes it: "at most 1 outstanding" means the reads have landed.
 #define PPMOE_STEP(cur, nxt, NKS, RB, Q, WB, LT, DO_READ, DO_STAGE)                                  \
   do {                                                                                               \
     PPMOE_MFMA(cur, 0, 0);                                                                           \
@@ -305,33 +310,33 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     PPMOE_MFMA(cur, 0, 1);                                                                           \
     if (DO_READ) PPMOE_READ_WGT(nxt, 0, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 1, 0);                                                                           \
-    if (DO_READ) PPMOE_READ_TOK(nxt, 1, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 1, 1);                                                                           \
-    if (DO_READ) PPMOE_READ_WGT(nxt, 1, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 0, 2);                                                                           \
-    if (DO_READ) PPMOE_READ_TOK(nxt, 2, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 0, 3);                                                                           \
-    if (DO_READ) PPMOE_READ_WGT(nxt, 2, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 1, 2);                                                                           \
-    if (DO_READ) PPMOE_READ_TOK(nxt, 3, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 1, 3);                                                                           \
-    if (DO_READ) PPMOE_READ_WGT(nxt, 3, NKS, RB);                                                    \
-    PPMOE_MFMA(cur, 2, 0);                                                                           \
     if (DO_STAGE) PPMOE_WRITE(4 * Q + 0, WB);                                                        \
-    PPMOE_MFMA(cur, 2, 1);                                                                           \
+    PPMOE_MFMA(cur, 1, 1);                                                                           \
+    if (DO_READ) PPMOE_READ_TOK(nxt, 1, NKS, RB);                                                    \
+    PPMOE_MFMA(cur, 0, 2);                                                                           \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 0, LT);                                             \
+    PPMOE_MFMA(cur, 0, 3);                                                                           \
+    if (DO_READ) PPMOE_READ_WGT(nxt, 1, NKS, RB);                                                    \
+    PPMOE_MFMA(cur, 1, 2);                                                                           \
     if (DO_STAGE) PPMOE_WRITE(4 * Q + 1, WB);                                                        \
+    PPMOE_MFMA(cur, 1, 3);                                                                           \
+    if (DO_READ) PPMOE_READ_TOK(nxt, 2, NKS, RB);                                                    \
+    PPMOE_MFMA(cur, 2, 0);                                                                           \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 1, LT);                                             \
+    PPMOE_MFMA(cur, 2, 1);                                                                           \
+    if (DO_READ) PPMOE_READ_WGT(nxt, 2, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 3, 0);                                                                           \
     if (DO_STAGE) PPMOE_WRITE(4 * Q + 2, WB);                                                        \
     PPMOE_MFMA(cur, 3, 1);                                                                           \
-    if (DO_STAGE) PPMOE_WRITE(4 * Q + 3, WB);                                                        \
+    if (DO_READ) PPMOE_READ_TOK(nxt, 3, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 2, 2);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 0, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 2, LT);                                             \
     PPMOE_MFMA(cur, 2, 3);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 1, LT);                                                              \
+    if (DO_READ) PPMOE_READ_WGT(nxt, 3, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 3, 2);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 2, LT);                                                              \
+    if (DO_STAGE) PPMOE_WRITE(4 * Q + 3, WB);                                                        \
     PPMOE_MFMA(cur, 3, 3);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 3, LT);                                                              \
+    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 3, LT);                                             \
   } while (0)
 
 
@@ -451,7 +456,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       PPMOE_READ_TOK(f0, 1, 0, 0); PPMOE_READ_WGT(f0, 1, 0, 0);
       PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
       PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
-      // (after the reads, so that the loop's first wait sees the same reads + 4 writes as every other)
+      // (after the reads: the loop's first wait, "at most 1 outstanding", then covers them)
       PPMOE_WRITE4(0, kBufBytes);
       if (stage_live(0)) {
 #pragma unroll
@@ -466,12 +471,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
         const uint32_t rb = ((t - kb) & 1) * kBufBytes, wb = kBufBytes - rb;
         const int lt = min(t + 2, last);
         // LDS operations complete in order: the reads being waited for were always followed by
-        // exactly 4 writes, so "at most 4 outstanding" means the reads have landed.
-        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+        // exactly one write, so "at most 1 outstanding" means the reads have landed.
+        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");
         PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
-        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f1)::"memory");
+        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f1)::"memory");
         PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
-        asm volatile("s_waitcnt lgkmcnt(4)" : PPMOE_TIE8(f0)::"memory");
+        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");
         PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
         // Every read of tile t and every write of tile t+1 by this wavefront has completed once
         // lgkmcnt is 0; after the barrier that holds for the whole block.
