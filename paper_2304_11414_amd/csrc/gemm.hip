@@ -306,7 +306,7 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                void* workspace, hipStream_t s) {
   if (max_rows == 0) return hipSuccess;
-  if (in_dtype == MOE_BF16 && (K % 64) == 0) {
+  if (in_dtype == MOE_BF16 && (K % 64) == 0 && K < (1 << 22)) {   // 32-bit panel offsets in the fast kernel
     return launch_grouped_gemm_fast(gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
                                     static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s);
   }

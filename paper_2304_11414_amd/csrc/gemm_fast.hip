@@ -409,9 +409,14 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       u32x4 stage[16];
       // Buffer loads: a scalar descriptor of the tile's panel (base = its first row), this lane's
       // 32-bit byte offset in a register and the k-tile offset as a scalar -- one address register
-      // per lane and no 64-bit vector add per load.
+      // per lane and no 64-bit vector add per load.  (Offsets are 32-bit: a panel of 256 rows must
+      // stay below 2 GiB, i.e. K < 4M.)
+      // The descriptor ends with the last valid row of the panel: an offset beyond it (there is none,
+      // rows are clamped) would read zeros instead of touching memory.
+      const int64_t panel_bytes = static_cast<int64_t>(row_lim + 1) * K * 2;
       const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<unsigned char*>(gbase), 0, 0x7fffffff, 0x00020000);
+          const_cast<unsigned char*>(gbase), 0,
+          static_cast<int>(panel_bytes < 0x7fffffff ? panel_bytes : 0x7fffffff), 0x00020000);
       auto gload = [&](int n, int t) {   // t: tile index along K
         stage[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[n], t * (BK * 2), 0);
       };
