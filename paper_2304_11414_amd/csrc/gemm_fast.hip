@@ -286,57 +286,59 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   do {                                                                                 \
     if (KIND == 0 || i < 2) lds_read16<i * 4096>(f[4 + i], wgt_a[ks] + (buf));          \
   } while (0)
-#define PPMOE_WRITE(n, buf) lds_write16<(n) * 1024>(wr_addr[(n) & 1] + (buf), stage[n])
-#define PPMOE_WRITE4(q, buf)     \
-  do {                           \
-    PPMOE_WRITE(4 * q + 0, buf); \
-    PPMOE_WRITE(4 * q + 1, buf); \
-    PPMOE_WRITE(4 * q + 2, buf); \
-    PPMOE_WRITE(4 * q + 3, buf); \
+// S: which of the two sets of staging registers (each holds one tile's share of this wavefront).
+#define PPMOE_WRITE(S, n, buf) lds_write16<(n) * 1024>(wr_addr[(n) & 1] + (buf), stage[(S) * 16 + (n)])
+#define PPMOE_WRITE4(S, q, buf)     \
+  do {                              \
+    PPMOE_WRITE(S, 4 * q + 0, buf); \
+    PPMOE_WRITE(S, 4 * q + 1, buf); \
+    PPMOE_WRITE(S, 4 * q + 2, buf); \
+    PPMOE_WRITE(S, 4 * q + 3, buf); \
   } while (0)
 
   // One k-step: 16 MFMAs on `cur`, the 8 fragment reads of the next k-step into `nxt`, and one
-  // quarter (4 instructions) of the staging traffic: write quarter Q to LDS, then reload it.
+  // quarter (4 instructions) of the staging traffic: write quarter Q of register set S to LDS, then
+  // reload it.
   // RB/WB: byte offsets of the buffer read from / written to.  NKS: k-step the reads are for.
   // One memory instruction per MFMA, and never two LDS writes in consecutive slots: four wavefronts
   // writing 1 KiB each in the same 32 cycles exceed what the LDS takes in, and the wavefront then
   // stalls at the next write (measured: 4 writes in 4 consecutive slots cost 56 cycles per k-step,
   // the same 4 writes one every 4 slots cost nothing).  The last LDS instruction of a k-step is a
   // write and every read precedes it: "at most 1 outstanding" means the reads have landed.
-#define PPMOE_STEP(cur, nxt, NKS, RB, Q, WB, LT, DO_READ, DO_STAGE)                                  \
+#define PPMOE_STEP(cur, nxt, NKS, RB, S, Q, WB, LT, DO_READ, DO_STAGE)                                  \
   do {                                                                                               \
     PPMOE_MFMA(cur, 0, 0);                                                                           \
     if (DO_READ) PPMOE_READ_TOK(nxt, 0, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 0, 1);                                                                           \
     if (DO_READ) PPMOE_READ_WGT(nxt, 0, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 1, 0);                                                                           \
-    if (DO_STAGE) PPMOE_WRITE(4 * Q + 0, WB);                                                        \
+    if (DO_STAGE) PPMOE_WRITE(S, 4 * Q + 0, WB);                                                     \
     PPMOE_MFMA(cur, 1, 1);                                                                           \
     if (DO_READ) PPMOE_READ_TOK(nxt, 1, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 0, 2);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 0, LT);                                             \
+    if (DO_STAGE && stage_live(Q)) gload(S, 4 * Q + 0, LT);                                          \
     PPMOE_MFMA(cur, 0, 3);                                                                           \
     if (DO_READ) PPMOE_READ_WGT(nxt, 1, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 1, 2);                                                                           \
-    if (DO_STAGE) PPMOE_WRITE(4 * Q + 1, WB);                                                        \
+    if (DO_STAGE) PPMOE_WRITE(S, 4 * Q + 1, WB);                                                     \
     PPMOE_MFMA(cur, 1, 3);                                                                           \
     if (DO_READ) PPMOE_READ_TOK(nxt, 2, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 2, 0);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 1, LT);                                             \
+    if (DO_STAGE && stage_live(Q)) gload(S, 4 * Q + 1, LT);                                          \
     PPMOE_MFMA(cur, 2, 1);                                                                           \
     if (DO_READ) PPMOE_READ_WGT(nxt, 2, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 3, 0);                                                                           \
-    if (DO_STAGE) PPMOE_WRITE(4 * Q + 2, WB);                                                        \
+    if (DO_STAGE) PPMOE_WRITE(S, 4 * Q + 2, WB);                                                     \
     PPMOE_MFMA(cur, 3, 1);                                                                           \
     if (DO_READ) PPMOE_READ_TOK(nxt, 3, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 2, 2);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 2, LT);                                             \
+    if (DO_STAGE && stage_live(Q)) gload(S, 4 * Q + 2, LT);                                          \
     PPMOE_MFMA(cur, 2, 3);                                                                           \
     if (DO_READ) PPMOE_READ_WGT(nxt, 3, NKS, RB);                                                    \
     PPMOE_MFMA(cur, 3, 2);                                                                           \
-    if (DO_STAGE) PPMOE_WRITE(4 * Q + 3, WB);                                                        \
+    if (DO_STAGE) PPMOE_WRITE(S, 4 * Q + 3, WB);                                                     \
     PPMOE_MFMA(cur, 3, 3);                                                                           \
-    if (DO_STAGE && stage_live(Q)) gload(4 * Q + 3, LT);                                             \
+    if (DO_STAGE && stage_live(Q)) gload(S, 4 * Q + 3, LT);                                          \
   } while (0)
 
 
@@ -406,19 +408,21 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       constexpr int KIND = decltype(kind_c)::value;
       // Staging registers and fragments belong to the segment: declared outside they would carry
       // their last values across the epilogue wherever a kind leaves some of them unwritten.
-      u32x4 stage[16];
+      u32x4 stage[32];
       // Buffer loads: a scalar descriptor of the tile's panel (base = its first row), this lane's
       // 32-bit byte offset in a register and the k-tile offset as a scalar -- one address register
       // per lane and no 64-bit vector add per load.  (Offsets are 32-bit: a panel of 256 rows must
       // stay below 2 GiB, i.e. K < 4M.)
       // The descriptor ends with the last valid row of the panel: an offset beyond it (there is none,
-      // rows are clamped) would read zeros instead of touching memory.
+      // rows are clamped) would read zeros instead of touching memory.  k-tiles past the end of the
+      // segment are loaded through an empty descriptor: every lane is out of range and gets zeros, so
+      // the MFMAs of a phantom tile add nothing (the loop runs tiles in pairs).
       const int64_t panel_bytes = static_cast<int64_t>(row_lim + 1) * K * 2;
-      const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<unsigned char*>(gbase), 0,
-          static_cast<int>(panel_bytes < 0x7fffffff ? panel_bytes : 0x7fffffff), 0x00020000);
-      auto gload = [&](int n, int t) {   // t: tile index along K
-        stage[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[n], t * (BK * 2), 0);
+      const int n_records = static_cast<int>(panel_bytes < 0x7fffffff ? panel_bytes : 0x7fffffff);
+      auto gload = [&](int set, int n, int t) {   // t: tile index along K
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned char*>(gbase), 0, t <= last ? n_records : 0, 0x00020000);
+        stage[set * 16 + n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[n], t * (BK * 2), 0);
       };
       bf16x8 f0[8], f1[8];
       // Small tile: every wavefront reads the token rows from row 0 and its own 64 weight rows.
@@ -437,24 +441,24 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       auto stage_live = [&](int q) -> bool { return KIND == 0 || is_b || (wave == 0 && q < KIND); };
 
       // ---- prologue ------------------------------------------------------------------------------
-      // The first tile goes through the registers into buffer 0; then the second is loaded, its first
-      // quarter written to buffer 1 and replaced by the first quarter of the third: the state every
-      // loop iteration starts in.  Tiles past the end of the segment are loaded from its last tile
-      // instead (never used), which keeps the loop free of branches.
+      // Two sets of staging registers: a load stays in flight for two tile times before it is written
+      // to LDS.  Set i & 1 holds tile kb + i (i = t - kb).  Here: tile kb goes through set 0 into
+      // buffer 0; sets 1 and 0 are loaded with tiles kb+1 and kb+2; quarter 0 of tile kb+1 is written
+      // to buffer 1 and replaced by quarter 0 of tile kb+3: the state every loop iteration starts in.
+      // Tiles past the end of the segment read as zeros, which keeps the loop free of branches.
+      auto gload_tile = [&](int set, int t) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (stage_live(q)) {
+        for (int q = 0; q < 4; ++q)
+          if (stage_live(q)) {
 #pragma unroll
-          for (int n = 4 * q; n < 4 * q + 4; ++n) gload(n, kb);
-        }
+            for (int n = 4 * q; n < 4 * q + 4; ++n) gload(set, n, t);
+          }
+      };
+      gload_tile(0, kb);
       __builtin_amdgcn_s_barrier();   // the previous segment's output transpose is out of LDS
-      PPMOE_WRITE4(0, 0); PPMOE_WRITE4(1, 0); PPMOE_WRITE4(2, 0); PPMOE_WRITE4(3, 0);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (stage_live(q)) {
-#pragma unroll
-          for (int n = 4 * q; n < 4 * q + 4; ++n) gload(n, min(kb + 1, last));
-        }
+      PPMOE_WRITE4(0, 0, 0); PPMOE_WRITE4(0, 1, 0); PPMOE_WRITE4(0, 2, 0); PPMOE_WRITE4(0, 3, 0);
+      gload_tile(1, kb + 1);
+      gload_tile(0, kb + 2);
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       PPMOE_READ_TOK(f0, 0, 0, 0); PPMOE_READ_WGT(f0, 0, 0, 0);
@@ -462,36 +466,42 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       PPMOE_READ_TOK(f0, 2, 0, 0); PPMOE_READ_WGT(f0, 2, 0, 0);
       PPMOE_READ_TOK(f0, 3, 0, 0); PPMOE_READ_WGT(f0, 3, 0, 0);
       // (after the reads: the loop's first wait, "at most 1 outstanding", then covers them)
-      PPMOE_WRITE4(0, kBufBytes);
+      PPMOE_WRITE4(1, 0, kBufBytes);
       if (stage_live(0)) {
 #pragma unroll
-        for (int n = 0; n < 4; ++n) gload(n, min(kb + 2, last));
+        for (int n = 0; n < 4; ++n) gload(1, n, kb + 3);
       }
 
       // ---- main loop -----------------------------------------------------------------------------
       // At the top of tile t (i = t - kb): buffer i&1 holds tile t (visible to all), f0 <- its k-step
-      // 0 (in flight), stage[4..15] hold quarters 1..3 of tile t+1 and stage[0..3] quarter 0 of tile
-      // t+2 (in flight), quarter 0 of tile t+1 is already in buffer (i+1)&1.
-      for (int t = kb; t < ke; ++t) {
-        const uint32_t rb = ((t - kb) & 1) * kBufBytes, wb = kBufBytes - rb;
-        const int lt = min(t + 2, last);
-        // LDS operations complete in order: the reads being waited for were always followed by
-        // exactly one write, so "at most 1 outstanding" means the reads have landed.
-        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");
-        PPMOE_STEP(f0, f1, 1, rb, 1, wb, lt, true, true);
-        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f1)::"memory");
-        PPMOE_STEP(f1, f0, 2, rb, 2, wb, lt, true, true);
-        asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");
-        PPMOE_STEP(f0, f1, 3, rb, 3, wb, lt, true, true);
-        // Every read of tile t and every write of tile t+1 by this wavefront has completed once
-        // lgkmcnt is 0; after the barrier that holds for the whole block.
-        asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");
-        __builtin_amdgcn_s_barrier();
-        // k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t
-        // is leaving, and is replaced in the registers by quarter 0 of tile t+3.
-        const int lt3 = min(t + 3, last);
-        PPMOE_STEP(f1, f0, 0, wb, 0, rb, lt3, true, true);
+      // 0 (in flight); quarter 0 of tile t+1 is already in buffer (i+1)&1; set (i+1)&1 holds quarters
+      // 1..3 of tile t+1 and quarter 0 of tile t+3; set i&1 holds tile t+2 (all in flight or landed).
+      // TILE(t, RB, WB, SA, SB): RB/WB the buffers of tiles t / t+1, SA = (i+1)&1, SB = i&1.
+#define PPMOE_TILE(t, RB, WB, SA, SB)                                                                \
+  do {                                                                                               \
+    const int lt = (t) + 3;                                                                          \
+    /* LDS operations complete in order: the reads being waited for were always followed by      */ \
+    /* exactly one write, so "at most 1 outstanding" means the reads have landed.                 */ \
+    asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");                                 \
+    PPMOE_STEP(f0, f1, 1, RB, SA, 1, WB, lt, true, true);                                            \
+    asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f1)::"memory");                                 \
+    PPMOE_STEP(f1, f0, 2, RB, SA, 2, WB, lt, true, true);                                            \
+    asm volatile("s_waitcnt lgkmcnt(1)" : PPMOE_TIE8(f0)::"memory");                                 \
+    PPMOE_STEP(f0, f1, 3, RB, SA, 3, WB, lt, true, true);                                            \
+    /* Every read of tile t and every write of tile t+1 by this wavefront has completed once     */ \
+    /* lgkmcnt is 0; after the barrier that holds for the whole block.                            */ \
+    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f1)::"memory");                                 \
+    __builtin_amdgcn_s_barrier();                                                                    \
+    /* k-step 3: prefetch k-step 0 of tile t+1; quarter 0 of tile t+2 goes into the buffer tile t */ \
+    /* is leaving, and is replaced in the registers by quarter 0 of tile t+4.                     */ \
+    const int lt4 = (t) + 4;                                                                         \
+    PPMOE_STEP(f1, f0, 0, WB, SB, 0, RB, lt4, true, true);                                           \
+  } while (0)
+      for (int t = kb; t < ke; t += 2) {   // (a segment of odd length ends with a phantom tile of zeros)
+        PPMOE_TILE(t, 0, kBufBytes, 1, 0);
+        PPMOE_TILE(t + 1, kBufBytes, 0, 0, 1);
       }
+#undef PPMOE_TILE
       asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_TIE8(f0)::"memory");
     };
     if (kind == 0) run_segment(std::integral_constant<int, 0>{});
