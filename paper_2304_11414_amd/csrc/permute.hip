@@ -25,7 +25,7 @@ __device__ __forceinline__ int read_slot(const int (&run)[kRegs], int e) {
   int v = 0;
 #pragma unroll
   for (int c = 0; c < kRegs; ++c)
-    if ((e >> 6) == c) v = __shfl(run[c], e & 63, 64);
+    if ((e >> 6) == c) v = __builtin_amdgcn_readlane(run[c], e & 63);
   return v;
 }
 
@@ -37,12 +37,9 @@ __device__ __forceinline__ void add_slot(int (&run)[kRegs], int e, int amount) {
 
 // Step 1.  seg_count[i * n_seg + seg] = number of assignments of segment seg that picked local
 // expert i.
-__global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __restrict__ expert_idx,
-                                                            int32_t* __restrict__ seg_count,
-                                                            int64_t n_assign, int n_seg,
-                                                            int local_begin, int n_local) {
-  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (seg >= n_seg) return;
+__device__ __forceinline__ void count_segment(const int32_t* __restrict__ expert_idx,
+                                              int32_t* seg_count, int seg, int64_t n_assign,
+                                              int n_seg, int local_begin, int n_local) {
   const int lane = lane_id();
   int run[kRegs] = {0, 0, 0, 0};
   const int64_t base = static_cast<int64_t>(seg) * kSegment;
@@ -56,7 +53,7 @@ __global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __res
     unsigned long long todo = __ballot(e >= 0);
     while (todo) {
       int leader = __ffsll(static_cast<long long>(todo)) - 1;
-      int e0 = __shfl(e, leader, 64);
+      int e0 = __builtin_amdgcn_readlane(e, leader);
       unsigned long long same = __ballot(e == e0);
       add_slot(run, e0, __popcll(same));
       todo &= ~same;
@@ -69,12 +66,18 @@ __global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __res
   }
 }
 
-// Step 2.  One wavefront per local expert: seg_base = exclusive scan of seg_count over segments,
-// totals[i] = queue length of expert i before any capacity clamp.
-__global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
-                                                          int32_t* __restrict__ seg_base,
-                                                          int32_t* __restrict__ totals, int n_seg) {
-  const int i = blockIdx.x;
+__global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __restrict__ expert_idx,
+                                                            int32_t* __restrict__ seg_count,
+                                                            int64_t n_assign, int n_seg,
+                                                            int local_begin, int n_local) {
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg < n_seg) count_segment(expert_idx, seg_count, seg, n_assign, n_seg, local_begin, n_local);
+}
+
+// Step 2.  One wavefront per local expert: seg_base = exclusive scan of seg_count over segments
+// (may be done in place), totals[i] = queue length of expert i before any capacity clamp.
+__device__ __forceinline__ void scan_expert(const int32_t* seg_count, int32_t* seg_base,
+                                            int32_t* totals, int i, int n_seg) {
   const int lane = lane_id();
   const int32_t* in = seg_count + static_cast<int64_t>(i) * n_seg;
   int32_t* out = seg_base + static_cast<int64_t>(i) * n_seg;
@@ -94,14 +97,18 @@ __global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restr
   if (lane == 0) totals[i] = carry;
 }
 
+__global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
+                                                          int32_t* __restrict__ seg_base,
+                                                          int32_t* __restrict__ totals, int n_seg) {
+  scan_expert(seg_count, seg_base, totals, blockIdx.x, n_seg);
+}
+
 // Step 3.
-__global__ __launch_bounds__(256) void rank_kernel(
-    const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ seg_base,
-    const int32_t* __restrict__ totals, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int64_t n_assign, int n_seg,
-    int local_begin, int n_local, int cap /* INT_MAX when unlimited */) {
-  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (seg >= n_seg) return;
+__device__ __forceinline__ void rank_segment(
+    const int32_t* __restrict__ expert_idx, const int32_t* seg_base, const int32_t* totals,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+    int32_t* __restrict__ inv_perm, int seg, int64_t n_assign, int n_seg, int local_begin,
+    int n_local, int cap /* INT_MAX when unlimited */) {
   const int lane = lane_id();
 
   // Kept queue lengths and their exclusive scan over the local experts (ascending expert id).
@@ -140,7 +147,7 @@ __global__ __launch_bounds__(256) void rank_kernel(
     unsigned long long todo = __ballot(e >= 0);
     while (todo) {
       int leader = __ffsll(static_cast<long long>(todo)) - 1;
-      int e0 = __shfl(e, leader, 64);
+      int e0 = __builtin_amdgcn_readlane(e, leader);
       unsigned long long same = __ballot(e == e0);
       int pos0 = read_slot(run, e0);   // queue position of the first of this group
       int off0 = read_slot(off, e0);
@@ -156,6 +163,17 @@ __global__ __launch_bounds__(256) void rank_kernel(
       if (row >= 0) perm[row] = static_cast<int32_t>(a);
     }
   }
+}
+
+__global__ __launch_bounds__(256) void rank_kernel(
+    const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ seg_base,
+    const int32_t* __restrict__ totals, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int64_t n_assign, int n_seg,
+    int local_begin, int n_local, int cap) {
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg < n_seg)
+    rank_segment(expert_idx, seg_base, totals, counts, offsets, perm, inv_perm, seg, n_assign, n_seg,
+                 local_begin, n_local, cap);
 }
 
 hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* expert_idx,
