@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(
 
   // U spans of 128 k-values per iteration: all their loads are issued before the first MFMA, so a
   // wavefront keeps U * (MT + NT) * 4 16-byte loads in flight.
-  constexpr int U = (NT * MT <= 4) ? 2 : 1;
+  constexpr int U = (NT * MT == 1) ? 4 : (NT * MT <= 4) ? 2 : 1;
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   for (int c0 = wave * 16; c0 < nchunk; c0 += 64 * U) {
     u32x4 a[U][MT][4], b[U][NT][4];

@@ -6,12 +6,14 @@
 // Block tile 256 x 256 x 64, four wavefronts (one per SIMD), each owning a 128 x 128 sub-tile as
 // 4 x 4 MFMA 32x32x16 bf16 accumulators (256 accumulator registers).
 //
-// What bounds this kernel is the L2 -> CU fetch path (a 256x256 tile needs 32 bytes per CU per clock
-// at full MFMA rate), so the loop is built around keeping that path evenly busy:
-//   * global loads are 16 bytes per lane, 8 lanes per row: every request is a whole 128-byte line;
-//   * loads are issued four at a time between MFMAs, all through the K loop, never in a burst;
-//   * a load stays in flight in registers for a whole tile time (64 MFMAs) before it is written to
-//     LDS, and LDS holds two tiles (written one tile ahead of use): three tiles deep in total;
+// A 256x256 tile needs 32 bytes per CU per clock from the L2 at full MFMA rate, about what the
+// fetch path of a CU sustains, so the loop is built around keeping that path evenly busy:
+//   * staging loads are buffer loads of 16 bytes per lane, 8 lanes per row: every request is a whole
+//     128-byte line;
+//   * exactly one memory instruction (LDS read, LDS write or load) is issued after each MFMA, all
+//     through the K loop, never in a burst;
+//   * a load stays in flight in registers for two tile times (two sets of staging registers) before
+//     it is written to LDS, and LDS holds two tiles (written one tile ahead of use);
 //   * one barrier per tile, placed after the third of the four k-steps, when every wavefront has
 //     already fetched the last fragments of the current tile: the fragments of the next tile are
 //     prefetched behind it, so no LDS latency is exposed at the tile boundary.
@@ -54,13 +56,6 @@ constexpr int kOperandBytes = BM * BK * 2;     // 32 KiB
 constexpr int kBufBytes = 2 * kOperandBytes;   // 64 KiB: one tile (tokens + weights)
 constexpr int kLdsBytes = 2 * kBufBytes;       // 128 KiB
 
-__device__ __forceinline__ float gelu_tanh(float u) {
-  // 0.5 u (1 + tanh(z)) = u / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3)
-  // exp and the reciprocal are single hardware instructions (about 1 ulp each), ample for a bf16 result.
-  const float z2 = -2.302208198f * u * fmaf(0.044715f * u, u, 1.0f);   // -2 sqrt(2/pi) log2(e) (u + 0.044715 u^3)
-  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z2));
-}
-
 // Reads one accumulator element where it lives (an accumulator register), at this point of the
 // program: without it the compiler copies all 256 accumulators to vector registers right after the
 // K loop and spills half of them.
@@ -70,15 +65,17 @@ __device__ __forceinline__ float read_acc(float a) {
   return v;
 }
 
-// Four at a time, stage by stage: the four dependency chains (mul, fma, mul, exp2, add, rcp, mul)
-// interleave, so the latency of each instruction is hidden by the other three elements.
+// GeLU, tanh form: 0.5 u (1 + tanh(z)) = u / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3).
+// exp2 and the reciprocal are single hardware instructions (about 1 ulp each), ample for a bf16
+// result.  Four at a time, stage by stage: the four dependency chains (mul, fma, mul, exp2, add,
+// rcp, mul) interleave, so the latency of each instruction is hidden by the other three elements.
 __device__ __forceinline__ f32x4 gelu_tanh4(f32x4 u) {
   // (the sched_barriers keep the compiler from folding the stages back into four serial chains)
   f32x4 z, e, r;
 #pragma unroll
   for (int i = 0; i < 4; ++i) z[i] = fmaf(0.044715f * u[i], u[i], 1.0f);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) z[i] = (-2.302208198f * u[i]) * z[i];
+  for (int i = 0; i < 4; ++i) z[i] = (-2.302208198f * u[i]) * z[i];   // -2 sqrt(2/pi) log2(e) (u + 0.044715 u^3)
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) e[i] = __builtin_amdgcn_exp2f(z[i]);
