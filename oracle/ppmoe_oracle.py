@@ -36,7 +36,10 @@ Parity unpinned by the paper (builder's stated definitions, pinned only by brute
 invariants in the tests):
   * the capacity limit (PPMoE abandons it, Section 4.1): C = ceil(cf * k * T / E); an assignment is
     kept iff fewer than C earlier assignments (ascending t*k + j) chose the same expert;
-  * the top-1 gate-weight convention (raw softmax probability vs renormalised to 1).
+  * the top-1 gate-weight convention (raw softmax probability vs renormalised to 1);
+  * the auxiliary balance loss ``l_aux`` that Algorithm 1 returns: the paper only says it follows
+    GShard (Section 4.1) and prints no formula.  ``aux_loss`` below is the GShard form; it is pinned
+    by closed forms and a scalar-loop restatement, not by anything the paper prints.
 """
 
 from __future__ import annotations
@@ -104,6 +107,28 @@ def gate(x, Wg, bias, k, renorm, logits_in=None, logits_dtype=np.float32):
     if renorm:
         gate_w = gate_w / gate_w.sum(axis=1, keepdims=True)
     return logits, expert_idx, gate_w
+
+
+def aux_loss(logits, expert_idx):
+    """Auxiliary load-balance loss returned by Algorithm 1 next to the output ("l_aux"); the paper
+    names GShard as its source (Section 4.1) and gives no formula, so this is the GShard form:
+
+        l_aux = E * sum_e  mean_prob[e] * first_fraction[e]
+
+    mean_prob[e]      = mean over tokens of the softmax probability of expert e,
+    first_fraction[e] = share of the tokens whose FIRST pick is expert e (also under top-2 gating,
+                        and before any capacity drop).
+    Returns dict(l_aux, mean_prob[E] float64, first_counts[E] int64).  Parity unpinned by the paper."""
+    logits = np.asarray(logits)
+    T, E = logits.shape
+    scores = softmax_rows(logits.astype(F64))
+    first = np.asarray(expert_idx).reshape(T, -1)[:, 0].astype(np.int64)
+    first_counts = np.bincount(first, minlength=E).astype(np.int64)
+    if T == 0:
+        return dict(l_aux=0.0, mean_prob=np.zeros(E, dtype=F64), first_counts=first_counts)
+    mean_prob = scores.sum(axis=0) / T
+    l_aux = float(E * np.sum(mean_prob * (first_counts / T)))
+    return dict(l_aux=l_aux, mean_prob=mean_prob, first_counts=first_counts)
 
 
 # ----------------------------------------------------------------------------------------------

@@ -372,3 +372,67 @@ def test_gate_weight_scales_the_expert_output():
     np.testing.assert_array_equal(a["expert_idx"], b["expert_idx"])
     np.testing.assert_allclose(b["out"] * a["gate_w"], a["out"] * b["gate_w"], rtol=1e-12, atol=1e-13)
     assert not np.allclose(a["gate_w"], b["gate_w"])
+
+
+# ---- auxiliary balance loss (GShard form; the paper prints no formula: pinned by closed forms) ----
+
+def test_aux_loss_closed_forms():
+    E, T = 8, 64
+    # all logits equal: probabilities 1/E, every token's first pick is expert 0 (ties -> lowest)
+    lg = np.zeros((T, E), dtype=np.float32)
+    idx = O.top_k_picks(lg, 1)
+    r = O.aux_loss(lg, idx)
+    assert r["first_counts"].tolist() == [T] + [0] * (E - 1)
+    np.testing.assert_allclose(r["mean_prob"], 1.0 / E, rtol=1e-15)
+    assert abs(r["l_aux"] - 1.0) < 1e-14            # E * (1/E * 1)
+    # perfectly balanced routing, token t prefers expert t mod E by a margin L: by symmetry the
+    # mean probability is exactly 1/E per expert and so is the first-pick share: l_aux = 1
+    L = 3.0
+    lg = np.zeros((T, E))
+    lg[np.arange(T), np.arange(T) % E] = L
+    r = O.aux_loss(lg, O.top_k_picks(lg, 1))
+    assert r["first_counts"].tolist() == [T // E] * E
+    np.testing.assert_allclose(r["mean_prob"], 1.0 / E, rtol=1e-14)
+    assert abs(r["l_aux"] - 1.0) < 1e-13
+    # every token prefers expert 2 with softmax probability q = e^a / (e^a + E - 1): l_aux = E q
+    a = 1.7
+    lg = np.zeros((T, E))
+    lg[:, 2] = a
+    q = math.exp(a) / (math.exp(a) + E - 1)
+    r = O.aux_loss(lg, O.top_k_picks(lg, 1))
+    assert abs(r["l_aux"] - E * q) < 1e-13
+    assert abs(r["mean_prob"][2] - q) < 1e-15 and abs(r["mean_prob"][0] - (1 - q) / (E - 1)) < 1e-15
+
+
+def test_aux_loss_against_scalar_loops_and_invariances():
+    rng = np.random.default_rng(11)
+    T, E = 37, 5
+    lg = rng.normal(size=(T, E)).astype(np.float32)
+    idx2 = O.top_k_picks(lg, 2)
+    r = O.aux_loss(lg, idx2)
+    # restated with scalar loops
+    mean_prob = [0.0] * E
+    counts = [0] * E
+    for t in range(T):
+        m = max(float(v) for v in lg[t])
+        ex = [math.exp(float(v) - m) for v in lg[t]]
+        z = sum(ex)
+        for e in range(E):
+            mean_prob[e] += ex[e] / z / T
+        best = 0
+        for e in range(1, E):
+            if float(lg[t, e]) > float(lg[t, best]):
+                best = e
+        counts[best] += 1
+    want = E * sum(mean_prob[e] * counts[e] / T for e in range(E))
+    assert r["first_counts"].tolist() == counts
+    np.testing.assert_allclose(r["mean_prob"], mean_prob, rtol=1e-13)
+    assert abs(r["l_aux"] - want) < 1e-13
+    # only the first pick counts: top-1 and top-2 gating of the same logits give the same loss
+    assert O.aux_loss(lg, O.top_k_picks(lg, 1))["l_aux"] == r["l_aux"]
+    # the order of the tokens does not matter (up to summation order)
+    p = rng.permutation(T)
+    assert abs(O.aux_loss(lg[p], idx2[p])["l_aux"] - r["l_aux"]) < 1e-13
+    # probabilities sum to one, shares sum to one; Cauchy-Schwarz-free bounds: 0 < l_aux <= E
+    assert abs(r["mean_prob"].sum() - 1.0) < 1e-14 and r["first_counts"].sum() == T
+    assert 0.0 < r["l_aux"] <= E
