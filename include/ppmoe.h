@@ -113,6 +113,21 @@ int moe_gate(const moe_config* cfg, const void* x, const void* Wg, const float* 
              const float* logits_in, float* logits_out, int32_t* expert_idx, float* gate_w,
              void* stream);
 
+/* Auxiliary load-balance loss, the second value Algorithm 1 returns ("l_aux").  The paper takes it
+ * from GShard (Section 4.1) and prints no formula; this is the GShard form:
+ *   l_aux = E * sum_e mean_prob[e] * first_counts[e] / T,
+ *   mean_prob[e]    = mean over the T tokens of softmax(logits)[t, e]      (float32),
+ *   first_counts[e] = number of tokens whose first pick expert_idx[t, 0] is e (also when top_k > 1;
+ *                     before any capacity drop).
+ * logits [T, E] float32 (what moe_gate wrote to logits_out); expert_idx [T, top_k] int32.
+ * l_aux: one float32 in device memory; mean_prob [E] float32 and first_counts [E] int32 in device
+ * memory, either may be NULL.  T == 0 gives zeros.  Sums have a fixed order (bitwise reproducible).
+ * workspace: device memory of at least moe_aux_workspace_bytes(cfg) bytes, overwritten. */
+size_t moe_aux_workspace_bytes(const moe_config* cfg);
+int moe_aux_loss(const moe_config* cfg, const float* logits, const int32_t* expert_idx, float* l_aux,
+                 float* mean_prob, int32_t* first_counts, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
 /* Tensor-index-slicing dispatch (Sections 3.3.1 and 3.3.3, the index selection that replaces the
  * first all-to-all; Algorithm 1: sliced_inputs).  Assignment id a = t*top_k + j.  The queue of an
  * expert is every assignment that picked it, in ascending a; with a capacity limit only the first

@@ -39,6 +39,8 @@ _PROTOTYPES = {
     "moe_dispatch_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_workspace_offsets": (c_int, [POINTER(MoeConfig), POINTER(MoeWorkspaceLayout)]),
     "moe_gate": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8),
+    "moe_aux_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
+    "moe_aux_loss": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 6 + [c_size_t, c_void_p]),
     "moe_slice_dispatch": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
     "moe_ffn_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
@@ -131,6 +133,16 @@ def moe_gate(cfg, x, Wg, bias, logits_in, logits_out, expert_idx, gate_w, stream
     _check(load_library().moe_gate(byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(logits_in),
                                    _ptr(logits_out), _ptr(expert_idx), _ptr(gate_w), _stream(stream)),
            "moe_gate")
+
+
+def moe_aux_workspace_bytes(cfg) -> int:
+    return load_library().moe_aux_workspace_bytes(byref(cfg))
+
+
+def moe_aux_loss(cfg, logits, expert_idx, l_aux, mean_prob, first_counts, workspace, stream=None):
+    _check(load_library().moe_aux_loss(byref(cfg), _ptr(logits), _ptr(expert_idx), _ptr(l_aux),
+                                       _ptr(mean_prob), _ptr(first_counts), _ptr(workspace),
+                                       _nbytes(workspace), _stream(stream)), "moe_aux_loss")
 
 
 def moe_slice_dispatch(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sliced, workspace,

@@ -146,6 +146,26 @@ int moe_gate(const moe_config* cfg, const void* x, const void* Wg, const float* 
                                 static_cast<hipStream_t>(stream)));
 }
 
+size_t moe_aux_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK) return 0;
+  return aux_scratch_bytes(*cfg);
+}
+
+int moe_aux_loss(const moe_config* cfg, const float* logits, const int32_t* expert_idx, float* l_aux,
+                 float* mean_prob, int32_t* first_counts, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (l_aux == nullptr || workspace == nullptr) return MOE_ERR_NULL;
+  if (cfg->T > 0 && (logits == nullptr || expert_idx == nullptr)) return MOE_ERR_NULL;
+  if (misaligned(logits) || misaligned(expert_idx) || misaligned(mean_prob) ||
+      misaligned(first_counts) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  if (workspace_bytes < aux_scratch_bytes(*cfg)) return MOE_ERR_WORKSPACE;
+  return hip_status(launch_aux_loss(*cfg, logits, expert_idx, l_aux, mean_prob, first_counts,
+                                    workspace, static_cast<hipStream_t>(stream)));
+}
+
 int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expert_idx,
                        int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                        void* x_sliced, void* workspace, size_t workspace_bytes, void* stream) {

@@ -54,6 +54,11 @@ hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
 hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
                           const float* gate_w, void* out, hipStream_t s);
 
+// Auxiliary balance loss from the logits and the picks; scratch: aux_scratch_bytes(c) bytes.
+size_t aux_scratch_bytes(const moe_config& c);
+hipError_t launch_aux_loss(const moe_config& c, const float* logits, const int32_t* expert_idx,
+                           float* l_aux, float* mean_prob, int32_t* first_counts, void* scratch,
+                           hipStream_t s);
 hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t s);
 // Register-resident MFMA loop on one block per CU (at most kMaxPersistentBlocks); sink: one float per thread.
 hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, int* blocks_out,

@@ -366,3 +366,57 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
     assert bool((out[zero_rows] == 0).all())
     assert bool(dl.torch.isfinite(out.float()).all())
     assert max_rel_err(got, ref_rows) < TOL["bf16"]
+
+
+# ---------------------------------------------------------------------------- auxiliary loss
+
+@pytest.mark.parametrize("T,E,k", [(1000, 8, 1), (8192, 8, 1), (777, 16, 2), (513, 64, 1), (65, 256, 8),
+                                   (64, 1, 1), (1, 5, 2), (4099, 3, 2)])
+def test_aux_loss_against_oracle(T, E, k):
+    """The balance loss next to the layer output (GShard form): first-pick counts bit-exact, mean
+    probabilities and the loss within the float32 bar, on logits with ties."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    logits = synth.random_logits(T, E, seed=3 * T + E, tie_fraction=0.2)
+    _, idx, _ = O.gate(None, None, None, k, False, logits_in=logits)
+    ref = O.aux_loss(logits, idx)
+    cfg = B.make_config(T, 64, 128, E, k)
+    d_logits = torch.from_numpy(logits).cuda()
+    d_idx = torch.from_numpy(idx).cuda()
+    l_aux = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    mean_prob = torch.full((E,), -1.0, dtype=torch.float32, device="cuda")
+    counts = torch.full((E,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.moe_aux_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xff)
+    B.moe_aux_loss(cfg, d_logits, d_idx, l_aux, mean_prob, counts, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(counts), ref["first_counts"])
+    assert_close(to_np(mean_prob), ref["mean_prob"], TOL["f32"], "mean_prob")
+    assert abs(float(l_aux.item()) - ref["l_aux"]) <= TOL["f32"] * abs(ref["l_aux"])
+    # a second call with only the loss requested gives the same bits
+    l2 = torch.empty(1, dtype=torch.float32, device="cuda")
+    B.moe_aux_loss(cfg, d_logits, d_idx, l2, None, None, ws)
+    torch.cuda.synchronize()
+    assert l2.item() == l_aux.item()
+
+
+def test_aux_loss_on_the_headline_router():
+    """Full-size headline workload: logits from the library's own router GEMM, loss against the
+    oracle evaluated on those logits (so both sides see the same float32 numbers)."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    lc = synth.CONFIGS[1]
+    inp = synth.make_inputs(lc, parts=("x", "Wg_t", "bias"))
+    dl = DeviceLayer(lc, inp)
+    logits, idx, _ = dl.run_gate()
+    ref = O.aux_loss(logits, idx)
+    cfg = B.config_from(lc)
+    l_aux = torch.empty(1, dtype=torch.float32, device="cuda")
+    counts = torch.empty(lc.E, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.moe_aux_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    B.moe_aux_loss(cfg, torch.from_numpy(logits).cuda(), torch.from_numpy(idx).cuda(), l_aux, None,
+                   counts, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(counts), ref["first_counts"])
+    assert abs(float(l_aux.item()) - ref["l_aux"]) <= TOL["f32"] * abs(ref["l_aux"])
+    assert 0.9 < ref["l_aux"] < 1.2      # a near-uniform router sits just above the balanced value 1
