@@ -164,6 +164,17 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
                    const void* W1, const void* W2, void* H, void* y_sliced, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/* Health of the expert-FFN calls that used `workspace` since the last check.  When an output tile
+ * is cut between compute units, the partial sums are handed over through the workspace with a
+ * bounded wait; this call copies the kernel's error word to the host (it SYNCHRONISES the stream)
+ * and sets *status (host) to 0: nothing went wrong; 1: a partial sum did not arrive within the
+ * wait limit, the affected output tile is incomplete; 2: writer and reader of a partial sum ran on
+ * different XCDs although the placement check at set-up said they would not.  A reported error is
+ * cleared.  layer_workspace != 0: `workspace` is the one given to moe_layer_forward; 0: the one
+ * given to moe_expert_ffn / _up / _down. */
+int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
+                  int32_t* status, void* stream);
+
 /* Combine (Sections 3.3.1/3.3.3, the index assignment that replaces the second all-to-all;
  * Algorithm 1: zeros_like + placement):
  *   out[t, :] = sum over j ascending with inv_perm[t, j] >= 0 of gate_w[t, j] * y_sliced[inv_perm[t, j], :]

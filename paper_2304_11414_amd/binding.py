@@ -46,6 +46,7 @@ _PROTOTYPES = {
     "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
     "moe_expert_ffn_down": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
     "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
+    "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
     "moe_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -177,6 +178,14 @@ def moe_expert_ffn(cfg, x_sliced, offsets, W1, W2, H, y_sliced, workspace, strea
     _check(load_library().moe_expert_ffn(byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1),
                                          _ptr(W2), _ptr(H), _ptr(y_sliced), _ptr(workspace),
                                          _nbytes(workspace), _stream(stream)), "moe_expert_ffn")
+
+
+def moe_ffn_check(cfg, workspace, layer_workspace, stream=None) -> int:
+    """0 when every hand-over of partial sums since the last check went through (synchronises)."""
+    status = c_int32(-1)
+    _check(load_library().moe_ffn_check(byref(cfg), _ptr(workspace), int(bool(layer_workspace)),
+                                        byref(status), _stream(stream)), "moe_ffn_check")
+    return status.value
 
 
 def moe_combine(cfg, y_sliced, inv_perm, gate_w, out, stream=None):

@@ -232,6 +232,25 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
   return moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, workspace, workspace_bytes, stream);
 }
 
+int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
+                  int32_t* status, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (workspace == nullptr || status == nullptr) return MOE_ERR_NULL;
+  const unsigned char* ws = static_cast<const unsigned char*>(workspace);
+  if (layer_workspace) {
+    moe_workspace_layout L;
+    size_t total = 0;
+    layout_of(*cfg, &L, &total);
+    ws += L.gemm;
+  }
+  uint32_t word = 0;
+  if (read_gemm_error_word(ws, &word, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MOE_ERR_HIP;
+  *status = (word & 0xffffff00u) == kGemmErrorMagic ? static_cast<int32_t>(word & 0xffu) : 0;
+  return MOE_OK;
+}
+
 int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_perm,
                 const float* gate_w, void* out, void* stream) {
   int st = check_config(cfg);

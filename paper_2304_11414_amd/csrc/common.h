@@ -73,6 +73,12 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
 // bf16 fast path of the above (K a multiple of 64): persistent, at most kMaxPersistentBlocks blocks.
 constexpr int kMaxPersistentBlocks = 256;
 size_t grouped_gemm_fast_workspace_bytes();
+// The fast GEMM leaves kGemmErrorMagic | code in one word of its workspace when a hand-over of
+// partial sums went wrong (1: a partial sum did not arrive within the spin limit, 2: writer and
+// reader were not on the same XCD although the set-up check said they would be).
+constexpr uint32_t kGemmErrorMagic = 0x4d6f4500u;
+// Copies that word to the host and synchronises the stream.
+hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream_t s);
 inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspace_bytes(); }
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,

@@ -214,6 +214,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
   __shared__ int contrib_foreign;
   const uint32_t my_xcc = xcc_id();
+  // A block's flag is down before it can be looked at: whatever the caller's workspace held, a stale
+  // word cannot pass for this launch's epoch (the readers poll tens of microseconds from now).
+  if (threadIdx.x == 0)
+    __hip_atomic_store(flags + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -535,14 +539,14 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
           uint32_t f;
           while (((f = __hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 4) != epoch) {
             if (++spins >= kSpinLimit) {
-              flags[gridDim.x] = 1u;   // left for a debugger: the result of this tile is incomplete
+              flags[kMaxPersistentBlocks] = kGemmErrorMagic | 1u;   // the result of this tile is incomplete
               break;
             }
             __builtin_amdgcn_s_sleep(16);
           }
           if ((f & 15u) != my_xcc) {   // the partial sums sit in another XCD's L2: the set-up check was wrong
             foreign = 1;
-            flags[gridDim.x] = 2u;
+            flags[kMaxPersistentBlocks] = kGemmErrorMagic | 2u;
           }
         }
         contrib[0] = n;
@@ -679,6 +683,25 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 
 }  // namespace fast
 
+hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream_t s) {
+  const float* slots = static_cast<const float*>(workspace);
+  const uint32_t* flags = reinterpret_cast<const uint32_t*>(
+      slots + static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats);
+  hipError_t e = hipMemcpyAsync(word, flags + kMaxPersistentBlocks, sizeof(uint32_t),
+                                hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return e;
+  if ((*word & 0xffffff00u) == kGemmErrorMagic) {   // reported once: lower it again
+    static const uint32_t zero = 0;
+    e = hipMemcpyAsync(const_cast<uint32_t*>(flags) + kMaxPersistentBlocks, &zero, sizeof(uint32_t),
+                       hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(s);
+  }
+  return e;
+}
+
 size_t grouped_gemm_fast_workspace_bytes() {
   // slots, flags (+1 word), one word per block for the placement check
   return static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats * sizeof(float) +
@@ -713,8 +736,10 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
   }();
   if (setup.err != hipSuccess) return setup.err;
   static std::atomic<uint32_t> launches{0};
-  uint32_t epoch = ++launches & 0x0fffffffu;   // 28 bits: the flag word also carries the XCD id
-  if (epoch == 0) epoch = ++launches & 0x0fffffffu;   // 0 means "flag down"
+  // 28 bits (the flag word also carries the XCD id), spread over the word so that small integers
+  // left in a recycled workspace do not look like an epoch; 0 means "flag down".
+  uint32_t epoch = (++launches * 0x9E3779B1u) >> 4;
+  if (epoch == 0) epoch = (++launches * 0x9E3779B1u) >> 4;
   float* slots = static_cast<float*>(workspace);
   uint32_t* flags = reinterpret_cast<uint32_t*>(slots + static_cast<size_t>(kMaxPersistentBlocks) * kSlotFloats);
   (void)max_rows;

@@ -124,6 +124,7 @@ class DeviceLayer:
         y = self.empty((max(self.rows, 1), c.d), et)
         ws = self.empty((B.moe_ffn_workspace_bytes(c),), t.uint8)
         B.moe_expert_ffn(c, xs, off, self.W1, self.W2, H, y, ws)
+        assert B.moe_ffn_check(c, ws, False) == 0, "a hand-over of partial sums failed"
         t.cuda.synchronize()
         return to_np(H[:n]), to_np(y[:n])
 
@@ -147,5 +148,6 @@ class DeviceLayer:
         out = self.empty((c.T, c.d), torch_dtype(self.lc.out_dtype))
         out.fill_(7.0)
         B.moe_layer_forward(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, ws)
+        assert B.moe_ffn_check(c, ws, True) == 0, "a hand-over of partial sums failed"
         t.cuda.synchronize()
         return out, B.workspace_views(c, ws)

@@ -420,3 +420,19 @@ def test_aux_loss_on_the_headline_router():
     np.testing.assert_array_equal(to_np(counts), ref["first_counts"])
     assert abs(float(l_aux.item()) - ref["l_aux"]) <= TOL["f32"] * abs(ref["l_aux"])
     assert 0.9 < ref["l_aux"] < 1.2      # a near-uniform router sits just above the balanced value 1
+
+
+def test_ffn_check_reads_and_clears_the_error_word():
+    """moe_ffn_check reports the word the GEMM kernel would leave (planted from the host here; no
+    kernel is made to fail), clears it, and ignores whatever else a recycled workspace holds."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    cfg = B.make_config(256, 64, 128, 4, 1)
+    ws = torch.empty(B.moe_ffn_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x11)                                   # small integers everywhere: not an error
+    assert B.moe_ffn_check(cfg, ws, False) == 0
+    word = (256 * 256 * 256 + 256) * 4               # slots of 256 x 256 floats, then the flags
+    for code in (1, 2):
+        ws[word:word + 4] = torch.tensor([code, 0x45, 0x6f, 0x4d], dtype=torch.uint8, device="cuda")
+        assert B.moe_ffn_check(cfg, ws, False) == code
+        assert B.moe_ffn_check(cfg, ws, False) == 0  # reported once
