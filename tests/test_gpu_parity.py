@@ -187,6 +187,8 @@ def ragged_offsets(counts):
     ("bf16", 512, 1024, [1024, 1000, 0, 24]),
     ("bf16", 4096, 256, [300, 3, 0, 257]),        # long K: tail tiles go through the cut k-tile stream
     ("bf16", 256, 4096, [129, 128, 600]),         # long K in the second GEMM
+    ("bf16", 8192, 256, [33, 64, 65, 32]),        # only small tiles, each cut between eight CUs
+    ("bf16", 2048, 512, [32, 33, 64, 65, 128, 129, 0, 1]),   # every small-tile height boundary
     ("f32", 64, 136, [70, 0, 64, 1]),
     ("f32", 256, 1024, [64, 64, 64, 64]),
 ])
