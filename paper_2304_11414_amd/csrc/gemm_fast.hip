@@ -27,9 +27,10 @@
 // the 8 XCDs, checked once per process with the XCC_ID register).  Row tiles are "big" (up to 256
 // rows) or, for the last at most 128 rows of an expert, "small" (computed as 32/64/128 rows x 256
 // columns with the four wavefronts side by side: a tail of a few rows costs a few MFMAs, not a tile).
-// Each XCD owns a contiguous eighth of the big-tile list and of the small-tile list, so the CUs
-// sharing an L2 work on the same panels.  Its CUs take the big tiles whole, in rounds; what is left
-// (big tiles when there are fewer than CUs, and the small tiles) is one stream of k-tiles cut into
+// Big tiles are taken whole, in rounds of the whole chip; the tile list is ordered in blocks of a
+// few row tiles x a few column tiles and an XCD runs one block per round, so the CUs sharing an L2
+// work on the same panels and neighbouring XCDs on neighbouring blocks.  What is left (big tiles
+// when there are fewer than CUs, and the small tiles) is one stream of k-tiles per XCD cut into
 // shares (stream-K).  A tile cut between CUs is finished by the CU that holds its first k-tile; the
 // others store their partial accumulators to a scratch slot and raise a flag.  Writer and reader of
 // a slot sit on the same XCD, so the hand-over goes through their shared L2 without device-scope
@@ -142,8 +143,14 @@ __device__ __forceinline__ void count_tiles(const int32_t* __restrict__ offsets,
   }
 }
 
+// Big tiles of one expert are listed in blocks of hm row tiles x hn column tiles (hm = up to 8,
+// hm * hn = the CUs of an XCD), row tile fastest inside a block, blocks along the columns first:
+// `cus` consecutive tiles -- what an XCD runs at the same time -- share hm token panels and hn
+// weight panels, and the blocks the eight XCDs run at the same time share their token panels.
+// (Listing an expert column by column instead gives every CU of an XCD its own token panel: with
+// 100 row tiles per expert each token panel was fetched again for every column tile.)
 __device__ __forceinline__ Tile big_tile_at(const int32_t* __restrict__ offsets, int n_exp,
-                                            int n_tiles, int small_rows, int tile) {
+                                            int n_tiles, int small_rows, int cus, int tile) {
   Tile t = {0, 0, 1, 0};
   int lo = offsets[0];
   for (int i = 0; i < n_exp; ++i) {
@@ -152,7 +159,14 @@ __device__ __forceinline__ Tile big_tile_at(const int32_t* __restrict__ offsets,
     expert_tiles(hi - lo, small_rows, big_m, small);
     const int here = big_m * n_tiles;
     if (tile < here) {
-      const int nt = tile / big_m, mt = tile - nt * big_m;
+      const int hm = min(big_m, 8), hn = max(1, cus / hm);
+      const int mb = tile / (hm * n_tiles);              // block row
+      const int t2 = tile - mb * hm * n_tiles;
+      const int hmb = min(hm, big_m - mb * hm);          // its height (the last one may be lower)
+      const int nb = t2 / (hmb * hn);                    // block inside the block row
+      const int t3 = t2 - nb * hmb * hn;
+      const int n_in = t3 / hmb, m_in = t3 - n_in * hmb;
+      const int mt = mb * hm + m_in, nt = nb * hn + n_in;
       t.expert = i;
       t.row0 = lo + mt * BM;
       t.rows = min(BM, hi - t.row0);
@@ -226,15 +240,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       (const __attribute__((address_space(3))) unsigned char*)lds));
 
   // ---- this block's work -----------------------------------------------------------------------
-  // Each XCD owns a contiguous eighth of the big tiles and an eighth of the small tiles (consecutive
-  // block ids go round-robin over the 8 XCDs, so `cus` = gridDim/8 blocks share an L2).
-  //  * With at least `cus` big tiles, its CUs take them whole, in rounds (round j: CU c takes big
-  //    tile j*cus + c of the XCD's run): neighbouring tiles run at the same time and in step along
-  //    K, which is what lets the L2 serve a panel once for several CUs.
-  //  * The small tiles -- and the big ones too when there are fewer than `cus` of them (few rows
-  //    per expert, or a narrow output) -- form one stream of k-tiles that is cut into `cus` equal
-  //    shares, so that a 3-row tail of an expert does not cost a CU a whole tile slot and every CU
-  //    has work.  A tile cut this way is finished by the CU that holds its first k-tile.
+  // Consecutive block ids go round-robin over the 8 XCDs, so `cus` = gridDim/8 blocks share an L2.
+  //  * Big tiles are taken whole, in rounds of the whole chip: in round j, XCD x runs the cus tiles
+  //    starting at (8 j + x) cus of the tile list, one per CU.  The list is ordered so that those
+  //    cus tiles are a block of a few row tiles x a few column tiles (see big_tile_at): they run at
+  //    the same time and in step along K, which is what lets the L2 serve a panel once for several
+  //    CUs.  What is left after the whole rounds (fewer than 8 cus tiles) is split evenly: one more,
+  //    partial round per XCD.
+  //  * The small tiles (an eighth per XCD) -- and the big ones too when there is no whole round and
+  //    an XCD has fewer than `cus` of them (few rows per expert, or a narrow output) -- form one
+  //    stream of k-tiles that is cut into shares, so that a 3-row tail of an expert does not cost a
+  //    CU a whole tile slot and every CU has work.  A tile cut this way is finished by the CU that
+  //    holds its first k-tile.
   // (Cutting the left-over big tiles of a last, partial round the same way was measured slower than
   // running that round: the CUs fall out of step along K, the L2 hit rate drops, and handing over
   // 256 KiB of partial sums costs about a tenth of a short tile per cut.)
@@ -244,13 +261,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   const int small_rows = kSmallRows;
   count_tiles(offsets, n_exp, n_tiles, small_rows, total_big, total_small);
   const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3, cus = gridDim.x >> 3;
-  const int bx0 = static_cast<int>(static_cast<int64_t>(total_big) * xcd / 8);
-  const int bx1 = static_cast<int>(static_cast<int64_t>(total_big) * (xcd + 1) / 8);
+  // Big tiles: whole rounds of the chip first -- in round j XCD x takes the cus tiles starting at
+  // (8 j + x) cus of the list, so at any time the eight XCDs work on neighbouring blocks -- then the
+  // remainder (fewer than 8 cus tiles), an eighth to each XCD.
+  const int chip = 8 * cus;
+  const int full_rounds = total_big / chip, rem = total_big - full_rounds * chip;
+  const int lx0 = full_rounds * chip + static_cast<int>(static_cast<int64_t>(rem) * xcd / 8);
+  const int lx1 = full_rounds * chip + static_cast<int>(static_cast<int64_t>(rem) * (xcd + 1) / 8);
   const int sx0 = static_cast<int>(static_cast<int64_t>(total_small) * xcd / 8);
   const int sx1 = static_cast<int>(static_cast<int64_t>(total_small) * (xcd + 1) / 8);
-  const bool cut_big = bx1 - bx0 < cus;
-  const int rounds = cut_big ? 0 : (bx1 - bx0 + cus - 1) / cus;
-  const int stream_big = cut_big ? bx1 - bx0 : 0;                  // big tiles at the head of the stream
+  const bool cut_big = full_rounds == 0 && lx1 - lx0 < cus;
+  const int rounds = cut_big ? 0 : full_rounds + (lx1 > lx0 ? 1 : 0);
+  const int stream_big = cut_big ? lx1 - lx0 : 0;                  // big tiles at the head of the stream
   const int64_t units = static_cast<int64_t>(stream_big + sx1 - sx0) * KT;
   // Shares shorter than kMinShare k-tiles are not worth their hand-over: fewer CUs then take part.
   const int takers = static_cast<int>(max(static_cast<int64_t>(1), min(static_cast<int64_t>(cus), units / kMinShare)));
@@ -348,16 +370,17 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     int tl = 0, kb = 0, ke = KT, kind = 0;
     Tile tc;
     if (round < rounds) {
-      const int b = bx0 + round * cus + cu;
+      const int b = round < full_rounds ? (round * 8 + xcd) * cus + cu : lx0 + cu;
+      const bool none = round >= full_rounds && b >= lx1;   // the last round may be partial
       ++round;
-      if (b >= bx1) continue;   // the last round may be partial (the stream, if any, still follows)
-      tc = big_tile_at(offsets, n_exp, n_tiles, small_rows, b);
+      if (none) continue;   // (the stream, if any, still follows)
+      tc = big_tile_at(offsets, n_exp, n_tiles, small_rows, cus, b);
     } else {
       tl = static_cast<int>(u / KT);
       kb = static_cast<int>(u - static_cast<int64_t>(tl) * KT);
       ke = static_cast<int>(min(static_cast<int64_t>(KT), kb + (u_end - u)));
       u += ke - kb;
-      tc = tl < stream_big ? big_tile_at(offsets, n_exp, n_tiles, small_rows, bx0 + tl)
+      tc = tl < stream_big ? big_tile_at(offsets, n_exp, n_tiles, small_rows, cus, lx0 + tl)
                            : small_tile_at(offsets, n_exp, n_tiles, small_rows, sx0 + tl - stream_big);
       kind = tile_kind(tc.rows, tl >= stream_big);
     }
