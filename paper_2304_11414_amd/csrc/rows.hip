@@ -85,11 +85,16 @@ hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStrea
 
 // ---- combine ----------------------------------------------------------------------------------
 
-template <typename T>
-struct Elems;  // how many elements a 16-byte piece holds and how to widen them
+// A thread produces 16 bytes of each output row it works on (n = 8 bf16 or 4 float32 elements), so
+// that the lanes of a wavefront store one contiguous kilobyte per instruction whatever the input
+// type; it reads the matching n elements of y: 16 bytes, or 8 when bf16 is combined into float32.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename TIn, int N>
+struct Piece;
 template <>
-struct Elems<bf16_t> {
-  static constexpr int n = 8;
+struct Piece<bf16_t, 8> {
+  typedef u32x4 type;
   __device__ static void widen(const u32x4& v, float* f) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -100,8 +105,18 @@ struct Elems<bf16_t> {
   }
 };
 template <>
-struct Elems<float> {
-  static constexpr int n = 4;
+struct Piece<bf16_t, 4> {
+  typedef u32x2 type;
+  __device__ static void widen(const u32x2& v, float* f) {
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xffff0000u);
+  }
+};
+template <>
+struct Piece<float, 4> {
+  typedef u32x4 type;
   __device__ static void widen(const u32x4& v, float* f) {
     f[0] = __uint_as_float(v.x);
     f[1] = __uint_as_float(v.y);
@@ -110,13 +125,14 @@ struct Elems<float> {
   }
 };
 
-// A block produces kRowsPerIter output rows per iteration; a thread, 16 bytes of y per pick and the
-// matching Elems<TIn>::n output elements of each of those rows.
+// A block produces kRowsPerIter output rows per iteration.
 template <typename TIn, typename TOut>
 __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
-    const u32x4* __restrict__ y, const int32_t* __restrict__ inv_perm,
+    const void* __restrict__ y_sliced, const int32_t* __restrict__ inv_perm,
     const float* __restrict__ gate_w, TOut* __restrict__ out, int T, int d, int top_k) {
-  constexpr int n = Elems<TIn>::n;
+  constexpr int n = 16 / sizeof(TOut);
+  typedef Piece<TIn, n> P;
+  const typename P::type* __restrict__ y = static_cast<const typename P::type*>(y_sliced);
   const int pieces_per_row = d / n;
   for (int t0 = blockIdx.x * kRowsPerIter; t0 < T; t0 += gridDim.x * kRowsPerIter) {
     for (int col = threadIdx.x; col < pieces_per_row; col += kCopyThreads) {
@@ -131,8 +147,7 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
           if (r >= 0) {
             const float w = gate_w[static_cast<int64_t>(t) * top_k + j];
             float f[n];
-            Elems<TIn>::widen(
-                __builtin_nontemporal_load(y + static_cast<int64_t>(r) * pieces_per_row + col), f);
+            P::widen(__builtin_nontemporal_load(y + static_cast<int64_t>(r) * pieces_per_row + col), f);
 #pragma unroll
             for (int e = 0; e < n; ++e) acc[i][e] = fmaf(w, f[e], acc[i][e]);
           }
@@ -143,7 +158,6 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
         if (t0 + i >= T) continue;
         TOut* o = out + static_cast<int64_t>(t0 + i) * d + static_cast<int64_t>(col) * n;
         if constexpr (sizeof(TOut) == 2) {
-          static_assert(n == 8, "bf16 output comes from bf16 input");
           u32x4 v;
           v.x = pack_bf16x2(acc[i][0], acc[i][1]);
           v.y = pack_bf16x2(acc[i][2], acc[i][3]);
@@ -151,11 +165,8 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
           v.w = pack_bf16x2(acc[i][6], acc[i][7]);
           __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(o));
         } else {
-#pragma unroll
-          for (int e = 0; e < n; e += 4) {
-            f32x4 v = {acc[i][e], acc[i][e + 1], acc[i][e + 2], acc[i][e + 3]};
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(o + e));
-          }
+          f32x4 v = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(o));
         }
       }
     }
@@ -165,11 +176,9 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
 hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
                           const float* gate_w, void* out, hipStream_t s) {
   if (c.T == 0) return hipSuccess;
-  const int n = c.in_dtype == MOE_BF16 ? 8 : 4;
-  (void)n;
   int64_t want = (static_cast<int64_t>(c.T) + kRowsPerIter - 1) / kRowsPerIter;
   int blocks = static_cast<int>(want < 256 * 8 ? want : 256 * 8);
-  const u32x4* y = static_cast<const u32x4*>(y_sliced);
+  const void* y = y_sliced;
   if (c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16)
     combine_kernel<bf16_t, bf16_t><<<blocks, kCopyThreads, 0, s>>>(
         y, inv_perm, gate_w, static_cast<bf16_t*>(out), c.T, c.d, c.top_k);
