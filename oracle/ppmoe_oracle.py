@@ -20,7 +20,7 @@ Arithmetic is float64 throughout, except that the gating module's logits are rou
 before softmax / top-k when ``logits_dtype`` says so (the paper runs the gating module in float32,
 Section 4.1), so that both sides take the integer top-k decision on the same numbers.
 
-Readings of points the paper leaves open (all stated again in the design notes):
+Readings of points the paper leaves open:
   * the gate weight returned by the gating function IS applied to the expert output
     (Section 3.1.4 describes scores per token; Algorithm 1 returns ``weights`` but never uses it);
   * placing expert outputs back is an accumulation (a token picked by two local experts under top-2
