@@ -49,7 +49,10 @@ class LayerConfig:
         return replace(self, **kw)
 
 
-# The five workloads.  CONFIGS[1] is the headline (d=2048, E=8, top-1, bf16).
+# The five workloads, plus a sixth that is not a MoE layer: with a single expert the layer is the
+# dense tensor-parallel FFN shard Y_i = GeLU(X A_i) B_i of Section 3.1.3 (one of 8 column/row slices
+# of a d -> 4d -> d FFN, float32 partial sum), run on the same kernels.
+# CONFIGS[1] is the headline (d=2048, E=8, top-1, bf16).
 # bias_scale of "zipf5" was found offline by bisection so that the heaviest expert receives about
 # 45 % of the 2*T assignments under top-2 (a token picks an expert at most once, so 50 % is the
 # ceiling); a CPU test checks the realised share.
@@ -63,6 +66,7 @@ CONFIGS = [
                 local_count=8, out_dtype="f32", seed=4),
     LayerConfig("wide_skewed_top2", T=32768, d=5120, F=20480, E=8, top_k=2, renorm_topk=True,
                 seed=5, bias_kind="zipf", bias_s=1.5, bias_scale=1.55),
+    LayerConfig("dense_tp_ffn_shard", T=8192, d=2048, F=1024, E=1, top_k=1, out_dtype="f32", seed=6),
 ]
 
 

@@ -297,6 +297,39 @@ def test_layer_is_bitwise_reproducible_and_ignores_workspace_contents():
     assert bool((a.view(dl.torch.int16) == b.view(dl.torch.int16)).all())
 
 
+def test_layer_replays_from_a_hip_graph():
+    """moe_layer_forward neither allocates nor synchronises, so it can be captured: the captured
+    layer is replayed several times, with the program's own eager work and synchronisations between
+    the replays, and every replay must give the eager result bit for bit (tiles cut between CUs
+    included: K = 4096 in the second GEMM, experts of ragged sizes)."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    lc = small_cfg(T=1500, d=256, F=4096, E=8, top_k=2, renorm_topk=True, seed=41)
+    inp = synth.make_inputs(lc)
+    dl = DeviceLayer(lc, inp)
+    eager, _ = dl.run_layer()                      # also the library's one-time set-up
+    c = dl.cfg
+    ws = dl.workspace(fill=0x5A)
+    out = torch.empty_like(eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        B.moe_layer_forward(c, dl.x, dl.Wg, dl.bias, dl.W1, dl.W2, out, ws)   # warm the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            B.moe_layer_forward(c, dl.x, dl.Wg, dl.bias, dl.W1, dl.W2, out, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        out.fill_(3.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert bool((out.view(torch.int16) == eager.view(torch.int16)).all()), f"replay {rep}"
+        assert B.moe_ffn_check(c, ws, True) == 0
+        again, _ = dl.run_layer(ws_fill=rep)       # eager work between the replays
+        assert bool((again.view(torch.int16) == eager.view(torch.int16)).all())
+
+
 def test_tensor_parallel_partials_sum_to_the_all_local_output():
     """Emulates the ranks of a tensor-parallel group on one GPU: each call holds a different block of
     experts; the partial outputs (what the all-reduce would sum) add up to the all-local output."""
@@ -329,7 +362,7 @@ def sampled_rows(info, T, n, seed):
     return np.array(sorted(rows))
 
 
-@pytest.mark.parametrize("ci,n_rows", [(1, 256), (2, 192), (3, 256), (4, 96)])
+@pytest.mark.parametrize("ci,n_rows", [(1, 256), (2, 192), (3, 256), (4, 96), (5, 256)])
 def test_layer_full_size_configs_sampled(ci, n_rows):
     lc = synth.CONFIGS[ci]
     print(f"[{lc.name}] drawing inputs", flush=True)
