@@ -2,7 +2,8 @@
 """Benchmark of the MoE-layer forward (Algorithm 1 without the all-reduce) on one MI355X.
 
 A "step" is one moe_layer_forward call: gate, permutation, slice, both grouped expert GEMMs and the
-combine, over one batch of synthetic tokens already resident in HBM.  The default workload is the
+combine (slice and combine done by the GEMMs' own loads and stores on the top-1 path), over one
+batch of synthetic tokens already resident in HBM.  The default workload is the
 headline configuration (T=8192, d=2048, F=8192, E=8, top-1, bf16).
 
 Prints ONE JSON line: layer tokens/s as `value`, a `roofline` object for the dominant kernel (the
@@ -178,7 +179,21 @@ def main():
         ms = timed(lambda: fl.append(B.moe_mfma_probe(100000, rnd, sink)), 3)
         ceilings[name] = round(fl[-1] / (ms * 1e-3) / 1e12, 1)
 
+    # The row-movement kernels on their own (K3 slice, K6 combine): on the fused top-1 path the layer
+    # does not run them, so their bandwidth is measured through the stage entry points, on the
+    # layer's own routing, back to back (launch gaps included).
     views = B.workspace_views(cfg, ws)
+    step()
+    torch.cuda.synchronize()
+    rows_max = max(B.moe_max_rows(cfg), 1)
+    xs = torch.empty((rows_max, lc.d), dtype=tdt, device="cuda")
+    ys = torch.empty((rows_max, lc.d), dtype=tdt, device="cuda").normal_()
+    out2 = torch.empty_like(out)
+    standalone_ms = {
+        "slice": timed(lambda: B.moe_slice_rows(cfg, dev["x"], views["perm"], views["offsets"], xs), 20),
+        "combine": timed(lambda: B.moe_combine(cfg, ys, views["inv_perm"], views["gate_w"], out2), 20)}
+    del xs, ys, out2
+
     counts = views["counts"].cpu().numpy()
     A = int(views["offsets"][-1].item())
     eb = 2 if lc.in_dtype == "bf16" else 4
@@ -207,10 +222,12 @@ def main():
         "ffn_frac_of_mfma_random_ceiling": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
                                                  / 1e12 / ceilings["mfma_random_tflops"], 4),
         "gate_gbs": round(bytes_gate / (st["gate"] * 1e-3) / 1e9, 1),
-        "slice_gbs": round(bytes_slice / (st["slice"] * 1e-3) / 1e9, 1),
-        "combine_gbs": round(bytes_combine / (st["combine"] * 1e-3) / 1e9, 1),
-        "slice_frac_of_hbm_peak": round(bytes_slice / (st["slice"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-        "combine_frac_of_hbm_peak": round(bytes_combine / (st["combine"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "layer_fuses_slice_and_combine": bool(B.moe_layer_fuses(cfg)),
+        "standalone_ms": {n: round(v, 5) for n, v in standalone_ms.items()},
+        "slice_gbs": round(bytes_slice / (standalone_ms["slice"] * 1e-3) / 1e9, 1),
+        "combine_gbs": round(bytes_combine / (standalone_ms["combine"] * 1e-3) / 1e9, 1),
+        "slice_frac_of_hbm_peak": round(bytes_slice / (standalone_ms["slice"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "combine_frac_of_hbm_peak": round(bytes_combine / (standalone_ms["combine"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
     }
     log("[bench] " + json.dumps(detail))
     # The dominant kernel is whichever of the two grouped GEMMs (same kernel template, equal FLOPs)

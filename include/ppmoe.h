@@ -144,6 +144,14 @@ int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expe
                        int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                        void* x_sliced, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The row gather of moe_slice_dispatch alone (Algorithm 1: hidden_states.index_select), from index
+ * lists already built:  x_sliced[r, :] = x[perm[r] / top_k, :]  for r < offsets[local_count].
+ * x [T, d] in_dtype; perm [moe_max_rows] int32 and offsets [local_count + 1] int32 as written by
+ * moe_slice_dispatch; x_sliced [moe_max_rows, d] in_dtype (rows beyond offsets[local_count] are
+ * left untouched). */
+int moe_slice_rows(const moe_config* cfg, const void* x, const int32_t* perm, const int32_t* offsets,
+                   void* x_sliced, void* stream);
+
 /* Local experts (Section 3.3.2: the N experts of a device; FFN of Section 3.1.3, GeLU(X A) B with
  * the tanh form of GeLU and no bias), evaluated as two grouped GEMMs over the packed rows:
  *   H[r, :]        = GeLU(x_sliced[r, :] . W1[i]^T)   for offsets[i] <= r < offsets[i+1]
@@ -192,6 +200,14 @@ int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_
 int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
                       const void* W1, const void* W2, void* out, void* workspace,
                       size_t workspace_bytes, void* const* stage_events, void* stream);
+
+/* 1 when moe_layer_forward runs `cfg` on its fused path (top_k == 1, bf16 in and out, d and F
+ * multiples of 64): the first expert GEMM reads the token rows through the permutation and the
+ * second one applies the gate weight and stores straight into `out` (Algorithm 1's index selection
+ * and its placement of the expert outputs, done by the GEMMs' own loads and stores), so the
+ * x_sliced and y_sliced regions of the workspace are left untouched; rows of `out` without a kept
+ * local pick are zeroed by a kernel of their own.  0 otherwise (every intermediate is written). */
+int moe_layer_fuses(const moe_config* cfg);
 
 /* Where moe_layer_forward keeps its intermediates inside `workspace` (byte offsets), so a caller
  * can inspect them after a run.  Any pointer may be NULL. */

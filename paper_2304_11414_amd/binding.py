@@ -42,6 +42,7 @@ _PROTOTYPES = {
     "moe_aux_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_aux_loss": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 6 + [c_size_t, c_void_p]),
     "moe_slice_dispatch": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
+    "moe_slice_rows": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_ffn_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
     "moe_expert_ffn_down": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
@@ -49,6 +50,7 @@ _PROTOTYPES = {
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
+    "moe_layer_fuses": (c_int, [POINTER(MoeConfig)]),
     "moe_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
     "moe_mfma_probe": (c_int, [c_int64, c_int, c_void_p, POINTER(c_double), c_void_p]),
     "moe_event_create": (c_int, [POINTER(c_void_p)]),
@@ -154,6 +156,11 @@ def moe_slice_dispatch(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sl
         _stream(stream)), "moe_slice_dispatch")
 
 
+def moe_slice_rows(cfg, x, perm, offsets, x_sliced, stream=None):
+    _check(load_library().moe_slice_rows(byref(cfg), _ptr(x), _ptr(perm), _ptr(offsets), _ptr(x_sliced),
+                                         _stream(stream)), "moe_slice_rows")
+
+
 def moe_ffn_workspace_bytes(cfg) -> int:
     return load_library().moe_ffn_workspace_bytes(byref(cfg))
 
@@ -201,6 +208,10 @@ def moe_layer_forward(cfg, x, Wg, bias, W1, W2, out, workspace, stage_events=Non
     _check(load_library().moe_layer_forward(
         byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), ev, _stream(stream)), "moe_layer_forward")
+
+
+def moe_layer_fuses(cfg) -> bool:
+    return bool(load_library().moe_layer_fuses(byref(cfg)))
 
 
 def moe_copy_bytes(src, dst, stream=None):

@@ -59,6 +59,9 @@ size_t aux_scratch_bytes(const moe_config& c);
 hipError_t launch_aux_loss(const moe_config& c, const float* logits, const int32_t* expert_idx,
                            float* l_aux, float* mean_prob, int32_t* first_counts, void* scratch,
                            hipStream_t s);
+// out[t, :] = +0 for every token t with inv_perm[t] < 0 (top-1 layout of inv_perm).
+hipError_t launch_zero_unrouted_rows(const moe_config& c, const int32_t* inv_perm, void* out,
+                                     hipStream_t s);
 hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t s);
 // Register-resident MFMA loop on one block per CU (at most kMaxPersistentBlocks); sink: one float per thread.
 hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, int* blocks_out,
@@ -66,9 +69,20 @@ hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, in
 
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
 // workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).
+// fuse (only where grouped_gemm_can_fuse says so): 1: packed row r of A is row aux_rows[r] of the
+// matrix given as A (first GEMM); 2: packed row r of the result, times aux_w[aux_rows[r]], is stored
+// as row aux_rows[r] of C (second GEMM; every such row of C is written at most once).
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
-                               void* workspace, hipStream_t s);
+                               void* workspace, hipStream_t s, int fuse = 0,
+                               const int32_t* aux_rows = nullptr, const float* aux_w = nullptr);
+inline bool grouped_gemm_is_fast(int in_dtype, int K) {
+  return in_dtype == MOE_BF16 && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
+}
+// Can A be read through a row list?  Its byte offsets must fit the 32-bit offsets of the loads.
+inline bool grouped_gemm_can_fuse(int in_dtype, int K, int64_t a_rows) {
+  return grouped_gemm_is_fast(in_dtype, K) && a_rows * K * 2 < 0x7fffffffLL;
+}
 
 // bf16 fast path of the above (K a multiple of 64): persistent, at most kMaxPersistentBlocks blocks.
 constexpr int kMaxPersistentBlocks = 256;
@@ -82,7 +96,8 @@ hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream
 inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspace_bytes(); }
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
-                                    int K, void* workspace, hipStream_t s);
+                                    int K, void* workspace, hipStream_t s, int fuse,
+                                    const int32_t* aux_rows, const float* aux_w);
 
 inline int64_t n_segments(const moe_config& c) {
   int64_t a = static_cast<int64_t>(c.T) * c.top_k;

@@ -304,12 +304,15 @@ static hipError_t ensure_lds_attr() {
 
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
-                               void* workspace, hipStream_t s) {
+                               void* workspace, hipStream_t s, int fuse, const int32_t* aux_rows,
+                               const float* aux_w) {
   if (max_rows == 0) return hipSuccess;
-  if (in_dtype == MOE_BF16 && (K % 64) == 0 && K < (1 << 22)) {   // 32-bit panel offsets in the fast kernel
+  if (grouped_gemm_is_fast(in_dtype, K)) {
     return launch_grouped_gemm_fast(gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
-                                    static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s);
+                                    static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s,
+                                    fuse, aux_rows, aux_w);
   }
+  if (fuse != 0) return hipErrorInvalidValue;   // the other kernels work on packed tensors only
   if (in_dtype == MOE_BF16) {
     hipError_t e = ensure_lds_attr();
     if (e != hipSuccess) return e;

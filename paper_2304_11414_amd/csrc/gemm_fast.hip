@@ -219,11 +219,17 @@ __global__ __launch_bounds__(kThreads) void xcc_probe_kernel(uint32_t* __restric
   if (threadIdx.x == 0) out[blockIdx.x] = xcc_id();
 }
 
-template <bool GELU>
+// FUSE: 0: A and C are the packed tensors.  1: the rows of A are read through a list (packed row r is
+// row aux_rows[r] of the matrix given as A): the index selection of Algorithm 1 done by the loads
+// of the first GEMM.  2: packed row r of the result is multiplied by aux_w[aux_rows[r]] and stored
+// as row aux_rows[r] of C: the placement of the expert outputs into the layer output done by the
+// stores of the second GEMM (top-1 only: a row of C is then written by at most one packed row).
+template <bool GELU, int FUSE>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
-    uint32_t* __restrict__ flags, uint32_t epoch, int same_l2) {
+    uint32_t* __restrict__ flags, uint32_t epoch, int same_l2, const int32_t* __restrict__ aux_rows,
+    const float* __restrict__ aux_w) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
   __shared__ int contrib_foreign;
@@ -411,14 +417,23 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 
     const int last = ke - 1;
     const int cols = min(BN, Nout - tc.col0);
+    const bool gathered = FUSE == 1 && !is_b;
     gbase = reinterpret_cast<const unsigned char*>(
         is_b ? B + (static_cast<size_t>(tc.expert) * Nout + tc.col0) * K
-             : A + static_cast<size_t>(tc.row0) * K);
+             : A + (gathered ? 0 : static_cast<size_t>(tc.row0) * K));
     const int row_lim = (is_b ? cols : tc.rows) - 1;
+    if (gathered) {
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
-      const int row = (wave & 1) * 128 + n * 8 + lrow;
-      goff[n] = (static_cast<uint32_t>(min(row, row_lim)) * K + piece * 8) * 2;
+      for (int n = 0; n < 16; ++n) {
+        const int row = (wave & 1) * 128 + n * 8 + lrow;
+        goff[n] = (static_cast<uint32_t>(aux_rows[tc.row0 + min(row, row_lim)]) * K + piece * 8) * 2;
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < 16; ++n) {
+        const int row = (wave & 1) * 128 + n * 8 + lrow;
+        goff[n] = (static_cast<uint32_t>(min(row, row_lim)) * K + piece * 8) * 2;
+      }
     }
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
@@ -441,7 +456,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       // rows are clamped) would read zeros instead of touching memory.  k-tiles past the end of the
       // segment are loaded through an empty descriptor: every lane is out of range and gets zeros, so
       // the MFMAs of a phantom tile add nothing (the loop runs tiles in pairs).
-      const int64_t panel_bytes = static_cast<int64_t>(row_lim + 1) * K * 2;
+      // (a gathered panel is the whole matrix: the rows the list names are rows of A, nothing to clamp)
+      const int64_t panel_bytes = gathered ? 0x7fffffff : static_cast<int64_t>(row_lim + 1) * K * 2;
       const int n_records = static_cast<int>(panel_bytes < 0x7fffffff ? panel_bytes : 0x7fffffff);
       auto gload = [&](int set, int n, int t) {   // t: tile index along K
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -596,6 +612,14 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     // The accumulators are read in exactly one place (one 32x32 block at a time), whichever way
     // they go: that keeps them in the accumulator registers until then.
     __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
+    float row_w[4] = {1.f, 1.f, 1.f, 1.f};   // FUSE == 2: gate weight of this lane's row of each row block
+    if (FUSE == 2 && !partial_only) {
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const int row = min(row_base + mi * 32 + frow, tc.rows - 1);
+        row_w[mi] = aux_w[aux_rows[tc.row0 + row]];
+      }
+    }
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
@@ -637,6 +661,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
           for (int q = 0; live && q < 4; ++q) {
             f32x4 w = v[q];
             if (GELU) w = gelu_tanh4(w);
+            if (FUSE == 2) w *= row_w[mi];
             const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
             const uint32_t a = epi_l + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
             const uint32_t lo = pack_bf16x2(w[0], w[1]), hi = pack_bf16x2(w[2], w[3]);
@@ -688,11 +713,24 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
                    : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
                    :
                    : "memory");
+      if (FUSE == 2) {
+        int dst[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int r = (i0 + j) * 4 + er;
-        if (r < nrow && ec * 8 < ncol)
-          *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v[j];
+        for (int j = 0; j < 8; ++j)
+          dst[j] = aux_rows[tc.row0 + row_base + min((i0 + j) * 4 + er, max(nrow, 1) - 1)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int r = (i0 + j) * 4 + er;
+          if (r < nrow && ec * 8 < ncol)
+            *reinterpret_cast<u32x4*>(C + static_cast<size_t>(dst[j]) * Nout + tc.col0 + col_base + ec * 8) = v[j];
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int r = (i0 + j) * 4 + er;
+          if (r < nrow && ec * 8 < ncol)
+            *reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(r) * Nout) = v[j];
+        }
       }
     }
   }
@@ -733,7 +771,8 @@ size_t grouped_gemm_fast_workspace_bytes() {
 
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
-                                    int K, void* workspace, hipStream_t s) {
+                                    int K, void* workspace, hipStream_t s, int fuse,
+                                    const int32_t* aux_rows, const float* aux_w) {
   using namespace fast;
   struct Setup {
     hipError_t err;
@@ -741,12 +780,15 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
   };
   static const Setup setup = [] {
     Setup r{hipSuccess, 0};
-    r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (r.err != hipSuccess) return r;
-    r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (r.err != hipSuccess) return r;
+    const void* kernels[] = {
+        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0>),
+        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0>),
+        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1>),
+        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2>)};
+    for (const void* k : kernels) {
+      r.err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+      if (r.err != hipSuccess) return r;
+    }
     int dev = 0, cus = 0;
     r.err = hipGetDevice(&dev);
     if (r.err != hipSuccess) return r;
@@ -780,12 +822,19 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
       if (host[b] != host[b & 7]) return 0;
     return 1;
   }();
-  if (gelu)
-    grouped_gemm_bf16_fast_kernel<true><<<setup.blocks, kThreads, kLdsBytes, s>>>(
-        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2);
-  else
-    grouped_gemm_bf16_fast_kernel<false><<<setup.blocks, kThreads, kLdsBytes, s>>>(
-        A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2);
+  // fuse: 0 none; 1 rows of A through aux_rows (first GEMM only); 2 weighted rows of C placed through
+  // aux_rows (second GEMM only)
+  if ((fuse == 1 && !gelu) || (fuse == 2 && gelu) || fuse < 0 || fuse > 2 ||
+      (fuse != 0 && aux_rows == nullptr) || (fuse == 2 && aux_w == nullptr))
+    return hipErrorInvalidValue;
+#define PPMOE_LAUNCH(G, F)                                                            \
+  grouped_gemm_bf16_fast_kernel<G, F><<<setup.blocks, kThreads, kLdsBytes, s>>>(      \
+      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, aux_rows, aux_w)
+  if (fuse == 1) PPMOE_LAUNCH(true, 1);
+  else if (fuse == 2) PPMOE_LAUNCH(false, 2);
+  else if (gelu) PPMOE_LAUNCH(true, 0);
+  else PPMOE_LAUNCH(false, 0);
+#undef PPMOE_LAUNCH
   return hipGetLastError();
 }
 

@@ -62,6 +62,28 @@ hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
   return hipGetLastError();
 }
 
+// ---- zero rows of the output (fused layer path) ---------------------------------------------
+// When the second GEMM places the expert outputs itself (top-1), rows of tokens without a kept local
+// pick are written by nobody: they are set to +0 here (Algorithm 1's zeros_like).
+__global__ __launch_bounds__(kCopyThreads) void zero_unrouted_rows_kernel(
+    const int32_t* __restrict__ inv_perm, u32x4* __restrict__ out, int T, int chunks_per_row) {
+  for (int t = blockIdx.x; t < T; t += gridDim.x) {
+    if (inv_perm[t] >= 0) continue;   // (uniform: one row per block iteration)
+    for (int col = threadIdx.x; col < chunks_per_row; col += kCopyThreads)
+      __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, out + static_cast<int64_t>(t) * chunks_per_row + col);
+  }
+}
+
+hipError_t launch_zero_unrouted_rows(const moe_config& c, const int32_t* inv_perm, void* out,
+                                     hipStream_t s) {
+  if (c.T == 0) return hipSuccess;
+  const int elem = c.out_dtype == MOE_BF16 ? 2 : 4;
+  const int blocks = c.T < 256 * 16 ? c.T : 256 * 16;
+  zero_unrouted_rows_kernel<<<blocks, kCopyThreads, 0, s>>>(inv_perm, static_cast<u32x4*>(out), c.T,
+                                                            c.d * elem / 16);
+  return hipGetLastError();
+}
+
 // ---- plain copy (reference kernel of known traffic, for calibrating hardware byte counters) ----
 
 __global__ __launch_bounds__(kCopyThreads) void copy_bytes_kernel(const u32x4* __restrict__ src,

@@ -142,6 +142,23 @@ def test_dispatch_random_orders(kw):
     check_dispatch(lc, idx, x)
 
 
+def test_slice_rows_alone_matches_the_dispatch_call():
+    """moe_slice_rows is the row gather of moe_slice_dispatch on its own."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    lc = small_cfg(T=777, d=264, E=8, top_k=2, capacity_factor=0.75, seed=13)
+    inp = synth.make_inputs(lc, parts=("x",))
+    idx = O.top_k_picks(synth.random_logits(lc.T, lc.E, seed=5, tie_fraction=0.1), lc.top_k)
+    dl = DeviceLayer(lc, inp)
+    counts, offsets, perm, inv, xs = dl.run_dispatch(idx)
+    out = torch.full((max(dl.rows, 1), lc.d), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.moe_slice_rows(dl.cfg, dl.x, torch.from_numpy(perm).cuda(), torch.from_numpy(offsets).cuda(), out)
+    torch.cuda.synchronize()
+    A = int(offsets[-1])
+    np.testing.assert_array_equal(to_np(out)[:A], xs[:A])
+    assert bool((out[A:] == 7.0).all())
+
+
 def test_dispatch_degenerate_orders():
     T = 1500
     # every token to one expert (the worst case of Section 3.2's footnote)
@@ -256,10 +273,14 @@ def compare_layer_full(lc, inp):
     np.testing.assert_array_equal(to_np(ws["perm"])[:A], ref["perm"])
     np.testing.assert_array_equal(to_np(ws["inv_perm"]), ref["inv_perm"])
     np.testing.assert_allclose(to_np(ws["gate_w"]), ref["gate_w"], rtol=2e-4, atol=1e-7)
-    np.testing.assert_array_equal(to_np(ws["x_sliced"])[:A], ref["x_sliced"])
     tol = TOL[lc.in_dtype]
     assert_close(to_np(ws["H"])[:A], ref["H"], tol, "H")
-    assert_close(to_np(ws["y_sliced"])[:A], ref["y_sliced"], tol, "y_sliced")
+    from paper_2304_11414_amd import binding as B
+    if not B.moe_layer_fuses(dl.cfg):
+        # (on the fused top-1 path the GEMMs read and place the rows themselves: the sliced tokens and
+        # the packed expert outputs are not materialised; the stage tests cover those kernels)
+        np.testing.assert_array_equal(to_np(ws["x_sliced"])[:A], ref["x_sliced"])
+        assert_close(to_np(ws["y_sliced"])[:A], ref["y_sliced"], tol, "y_sliced")
     out_np = to_np(out)
     assert_close(out_np, ref["out"], tol, "out")
     zero_rows = ~(ref["inv_perm"] >= 0).any(axis=1)
@@ -281,6 +302,10 @@ def test_layer_config1_fp32_full():
     dict(T=1500, d=256, F=1024, E=64, top_k=1, local_begin=8, local_count=8, out_dtype="f32", seed=24),
     dict(T=640, d=128, F=256, E=1, top_k=1, seed=25),
     dict(T=700, d=64, F=128, E=4, top_k=4, in_dtype="f32", out_dtype="f32", seed=26),
+    # fused top-1 path with rows nobody places: a subset of the experts, then a capacity that drops
+    dict(T=1500, d=256, F=1024, E=16, top_k=1, local_begin=4, local_count=8, seed=27),
+    dict(T=2000, d=128, F=4096, E=8, top_k=1, capacity_factor=0.5, bias_kind="zipf", bias_s=1.1,
+         seed=28),
 ])
 def test_layer_medium_full(kw):
     lc = small_cfg(**kw)
