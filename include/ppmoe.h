@@ -194,7 +194,9 @@ int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_
 /* The whole layer (Algorithm 1 up to, not including, reduce_from_tensor_parallel_region): the six
  * stages above on one stream with no host round trip.  Intermediates live in `workspace`
  * (>= moe_workspace_bytes(cfg)); `out` [T, d] out_dtype is the partial sum this device would
- * contribute to the all-reduce.
+ * contribute to the all-reduce.  Where moe_layer_fuses(cfg) says so, the slice and the combine are
+ * carried out by the loads of the first and the stores of the second expert GEMM and x_sliced /
+ * y_sliced are not written; everything else in the workspace is.
  * stage_events: NULL, or a HOST array of MOE_NUM_STAGES + 1 hipEvent_t handles (as void*) that are
  * recorded on `stream` around the stages, for timing. */
 int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
