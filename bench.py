@@ -222,7 +222,8 @@ def main():
         "ffn_frac_of_mfma_random_ceiling": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
                                                  / 1e12 / ceilings["mfma_random_tflops"], 4),
         "gate_gbs": round(bytes_gate / (st["gate"] * 1e-3) / 1e9, 1),
-        "layer_fuses_slice_and_combine": bool(B.moe_layer_fuses(cfg)),
+        "layer_fuses": {"slice": bool(B.moe_layer_fuses(cfg) & B.MOE_FUSE_SLICE),
+                        "combine": bool(B.moe_layer_fuses(cfg) & B.MOE_FUSE_COMBINE)},
         "standalone_ms": {n: round(v, 5) for n, v in standalone_ms.items()},
         "slice_gbs": round(bytes_slice / (standalone_ms["slice"] * 1e-3) / 1e9, 1),
         "combine_gbs": round(bytes_combine / (standalone_ms["combine"] * 1e-3) / 1e9, 1),

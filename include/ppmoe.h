@@ -203,12 +203,16 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
                       const void* W1, const void* W2, void* out, void* workspace,
                       size_t workspace_bytes, void* const* stage_events, void* stream);
 
-/* 1 when moe_layer_forward runs `cfg` on its fused path (top_k == 1, bf16 in and out, d and F
- * multiples of 64): the first expert GEMM reads the token rows through the permutation and the
- * second one applies the gate weight and stores straight into `out` (Algorithm 1's index selection
- * and its placement of the expert outputs, done by the GEMMs' own loads and stores), so the
- * x_sliced and y_sliced regions of the workspace are left untouched; rows of `out` without a kept
- * local pick are zeroed by a kernel of their own.  0 otherwise (every intermediate is written). */
+/* Which stages moe_layer_forward folds into the expert GEMMs for `cfg` (bf16 input, d a multiple
+ * of 64): a mask of
+ *   MOE_FUSE_SLICE    the first GEMM reads the token rows through the permutation (Algorithm 1's
+ *                     index selection done by its loads): x_sliced is not written;
+ *   MOE_FUSE_COMBINE  (top_k == 1, bf16 output, F a multiple of 64) the second GEMM applies the gate
+ *                     weight and stores straight into `out` (the placement of the expert outputs
+ *                     done by its stores): y_sliced is not written; rows of `out` without a kept
+ *                     local pick are zeroed by a kernel of their own.
+ * 0: every intermediate is written. */
+enum { MOE_FUSE_SLICE = 1, MOE_FUSE_COMBINE = 2 };
 int moe_layer_fuses(const moe_config* cfg);
 
 /* Where moe_layer_forward keeps its intermediates inside `workspace` (byte offsets), so a caller

@@ -210,8 +210,12 @@ def moe_layer_forward(cfg, x, Wg, bias, W1, W2, out, workspace, stage_events=Non
         workspace.numel() * workspace.element_size(), ev, _stream(stream)), "moe_layer_forward")
 
 
-def moe_layer_fuses(cfg) -> bool:
-    return bool(load_library().moe_layer_fuses(byref(cfg)))
+MOE_FUSE_SLICE, MOE_FUSE_COMBINE = 1, 2
+
+
+def moe_layer_fuses(cfg) -> int:
+    """Mask of MOE_FUSE_SLICE / MOE_FUSE_COMBINE: the stages moe_layer_forward folds into the GEMMs."""
+    return load_library().moe_layer_fuses(byref(cfg))
 
 
 def moe_copy_bytes(src, dst, stream=None):

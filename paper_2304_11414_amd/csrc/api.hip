@@ -275,17 +275,21 @@ int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_
                                    static_cast<hipStream_t>(stream)));
 }
 
-// Top-1 on the bf16 fast path: the first GEMM reads the token rows through the permutation and the
-// second one multiplies by the gate weight and stores straight into the layer output, so neither the
-// sliced copy of the tokens nor the packed expert outputs are materialised.
-static bool layer_fuses(const moe_config& c) {
-  return c.top_k == 1 && c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16 &&
-         grouped_gemm_can_fuse(c.in_dtype, c.d, c.T) && grouped_gemm_is_fast(c.in_dtype, c.F);
+// What moe_layer_forward folds into the expert GEMMs on the bf16 fast path.  Bit 0: the first GEMM
+// reads the token rows through the permutation, so the sliced copy of the tokens is not made.
+// Bit 1 (top-1, bf16 output): the second GEMM multiplies by the gate weight and stores straight into
+// the layer output, so the packed expert outputs are not made either.
+static int layer_fuses(const moe_config& c) {
+  if (!grouped_gemm_can_fuse(c.in_dtype, c.d, c.T)) return 0;
+  int f = MOE_FUSE_SLICE;
+  if (c.top_k == 1 && c.out_dtype == MOE_BF16 && grouped_gemm_is_fast(c.in_dtype, c.F))
+    f |= MOE_FUSE_COMBINE;
+  return f;
 }
 
 int moe_layer_fuses(const moe_config* cfg) {
   if (check_config(cfg) != MOE_OK) return 0;
-  return layer_fuses(*cfg) ? 1 : 0;
+  return layer_fuses(*cfg);
 }
 
 int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
@@ -337,33 +341,32 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
   PPMOE_TRY(mark(MOE_STAGE_PERMUTE));
   PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm,
                            reinterpret_cast<int32_t*>(ws + L.scratch), s));
-  if (layer_fuses(c)) {
-    // (the slice and combine stages are empty here; their events are still recorded)
-    PPMOE_TRY(mark(MOE_STAGE_SLICE));
-    PPMOE_TRY(mark(MOE_STAGE_FFN_UP));
+  // (a stage folded into a GEMM is empty; its events are still recorded)
+  const int fuses = layer_fuses(c);
+  PPMOE_TRY(mark(MOE_STAGE_SLICE));
+  if (!(fuses & MOE_FUSE_SLICE)) PPMOE_TRY(launch_slice(c, x, perm, offsets, x_sliced, rows, s));
+  PPMOE_TRY(mark(MOE_STAGE_FFN_UP));
+  if (fuses & MOE_FUSE_SLICE)
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x, W1, H, offsets, c.local_count, rows, c.F, c.d,
-                                  ws + L.gemm, s, 1, perm, nullptr));
-    PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
+                                  ws + L.gemm, s, 1, perm, nullptr, c.top_k));
+  else
+    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x_sliced, W1, H, offsets, c.local_count, rows,
+                                  c.F, c.d, ws + L.gemm, s));
+  PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
+  if (fuses & MOE_FUSE_COMBINE) {
     // Tokens without a kept local pick exist only with a subset of the experts or a capacity limit.
     if (c.local_count < c.E || c.capacity_factor > 0.f)
       PPMOE_TRY(launch_zero_unrouted_rows(c, inv_perm, out, s));
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, out, offsets, c.local_count, rows, c.d,
                                   c.F, ws + L.gemm, s, 2, perm, gate_w));
     PPMOE_TRY(mark(MOE_STAGE_COMBINE));
-    PPMOE_TRY(mark(MOE_NUM_STAGES));
   } else {
-    PPMOE_TRY(mark(MOE_STAGE_SLICE));
-    PPMOE_TRY(launch_slice(c, x, perm, offsets, x_sliced, rows, s));
-    PPMOE_TRY(mark(MOE_STAGE_FFN_UP));
-    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x_sliced, W1, H, offsets, c.local_count, rows,
-                                  c.F, c.d, ws + L.gemm, s));
-    PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, y_sliced, offsets, c.local_count, rows,
                                   c.d, c.F, ws + L.gemm, s));
     PPMOE_TRY(mark(MOE_STAGE_COMBINE));
     PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s));
-    PPMOE_TRY(mark(MOE_NUM_STAGES));
   }
+  PPMOE_TRY(mark(MOE_NUM_STAGES));
 #undef PPMOE_TRY
   return MOE_OK;
 }

@@ -69,13 +69,14 @@ hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, in
 
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
 // workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).
-// fuse (only where grouped_gemm_can_fuse says so): 1: packed row r of A is row aux_rows[r] of the
-// matrix given as A (first GEMM); 2: packed row r of the result, times aux_w[aux_rows[r]], is stored
+// fuse (only where grouped_gemm_can_fuse says so): 1: packed row r of A is row aux_rows[r] / aux_div
+// of the matrix given as A (first GEMM); 2: packed row r of the result, times aux_w[aux_rows[r]], is stored
 // as row aux_rows[r] of C (second GEMM; every such row of C is written at most once).
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                void* workspace, hipStream_t s, int fuse = 0,
-                               const int32_t* aux_rows = nullptr, const float* aux_w = nullptr);
+                               const int32_t* aux_rows = nullptr, const float* aux_w = nullptr,
+                               int aux_div = 1);
 inline bool grouped_gemm_is_fast(int in_dtype, int K) {
   return in_dtype == MOE_BF16 && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
 }
@@ -97,7 +98,7 @@ inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspac
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
-                                    const int32_t* aux_rows, const float* aux_w);
+                                    const int32_t* aux_rows, const float* aux_w, int aux_div);
 
 inline int64_t n_segments(const moe_config& c) {
   int64_t a = static_cast<int64_t>(c.T) * c.top_k;

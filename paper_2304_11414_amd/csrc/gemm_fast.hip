@@ -220,8 +220,8 @@ __global__ __launch_bounds__(kThreads) void xcc_probe_kernel(uint32_t* __restric
 }
 
 // FUSE: 0: A and C are the packed tensors.  1: the rows of A are read through a list (packed row r is
-// row aux_rows[r] of the matrix given as A): the index selection of Algorithm 1 done by the loads
-// of the first GEMM.  2: packed row r of the result is multiplied by aux_w[aux_rows[r]] and stored
+// row aux_rows[r] / aux_div of the matrix given as A): the index selection of Algorithm 1 done by
+// the loads of the first GEMM.  2: packed row r of the result is multiplied by aux_w[aux_rows[r]] and stored
 // as row aux_rows[r] of C: the placement of the expert outputs into the layer output done by the
 // stores of the second GEMM (top-1 only: a row of C is then written by at most one packed row).
 template <bool GELU, int FUSE>
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
     uint32_t* __restrict__ flags, uint32_t epoch, int same_l2, const int32_t* __restrict__ aux_rows,
-    const float* __restrict__ aux_w) {
+    const float* __restrict__ aux_w, int aux_div) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
   __shared__ int contrib_foreign;
@@ -426,7 +426,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 #pragma unroll
       for (int n = 0; n < 16; ++n) {
         const int row = (wave & 1) * 128 + n * 8 + lrow;
-        goff[n] = (static_cast<uint32_t>(aux_rows[tc.row0 + min(row, row_lim)]) * K + piece * 8) * 2;
+        const int a = aux_rows[tc.row0 + min(row, row_lim)];
+        goff[n] = (static_cast<uint32_t>(aux_div == 1 ? a : a / aux_div) * K + piece * 8) * 2;
       }
     } else {
 #pragma unroll
@@ -772,7 +773,7 @@ size_t grouped_gemm_fast_workspace_bytes() {
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
-                                    const int32_t* aux_rows, const float* aux_w) {
+                                    const int32_t* aux_rows, const float* aux_w, int aux_div) {
   using namespace fast;
   struct Setup {
     hipError_t err;
@@ -825,11 +826,12 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
   // fuse: 0 none; 1 rows of A through aux_rows (first GEMM only); 2 weighted rows of C placed through
   // aux_rows (second GEMM only)
   if ((fuse == 1 && !gelu) || (fuse == 2 && gelu) || fuse < 0 || fuse > 2 ||
-      (fuse != 0 && aux_rows == nullptr) || (fuse == 2 && aux_w == nullptr))
+      (fuse != 0 && aux_rows == nullptr) || (fuse == 2 && aux_w == nullptr) || aux_div < 1 ||
+      (fuse == 2 && aux_div != 1))
     return hipErrorInvalidValue;
 #define PPMOE_LAUNCH(G, F)                                                            \
   grouped_gemm_bf16_fast_kernel<G, F><<<setup.blocks, kThreads, kLdsBytes, s>>>(      \
-      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, aux_rows, aux_w)
+      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, aux_rows, aux_w, aux_div)
   if (fuse == 1) PPMOE_LAUNCH(true, 1);
   else if (fuse == 2) PPMOE_LAUNCH(false, 2);
   else if (gelu) PPMOE_LAUNCH(true, 0);
