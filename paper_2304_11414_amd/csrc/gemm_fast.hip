@@ -116,9 +116,8 @@ __device__ __forceinline__ int tile_kind(int rows, bool small) {
 
 // An expert's rows are cut into m-tiles of BM; its last m-tile is "small" when it has at most
 // kSmallRows rows.  The tile list has two parts: all the other ("big") tiles, ordered expert-major,
-// then n-tile, then m-tile (m fastest); then the small tiles, ordered expert-major, then n-tile.
-// (Only when K is long: with a short K loop the hand-over of partial sums costs more than letting
-// the tail tile take a slot of a round; measured on K = 2048 against K = 8192.)
+// in blocks of row tiles x column tiles (see big_tile_at); then the small tiles, ordered
+// expert-major, then n-tile.
 constexpr int kSmallRows = 128;
 #ifndef PPMOE_MIN_SHARE
 #define PPMOE_MIN_SHARE 16
