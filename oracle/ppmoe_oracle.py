@@ -137,10 +137,16 @@ def aux_loss(logits, expert_idx):
 # ----------------------------------------------------------------------------------------------
 
 def capacity(capacity_factor, k, T, E):
-    """Per-expert queue limit, or None for "no limit" (what PPMoE does, Section 4.1)."""
+    """Per-expert queue limit, or None for "no limit" (what PPMoE does, Section 4.1).
+
+    The factor is a single-precision number (the field of the layer's configuration record is a
+    float32), so it is rounded to float32 first; the product is then formed left to right in
+    float64.  With a factor that float32 cannot hold this decides whether a queue keeps one
+    assignment more: float32(1.2) = 1.2000000476837158203125, so 1.2 * 20 / 4 gives 7, not 6."""
     if capacity_factor is None or capacity_factor <= 0:
         return None
-    return int(math.ceil(float(capacity_factor) * k * T / E))
+    cf = float(np.float32(capacity_factor))
+    return int(math.ceil(cf * k * T / E))
 
 
 def dispatch(expert_idx, E, local_begin, local_count, cap=None):

@@ -50,7 +50,10 @@ def test_capacity_and_row_bounds_match_oracle(lib):
         cap = O.capacity(lc.capacity_factor, lc.top_k, lc.T, lc.E)
         assert B.moe_capacity(cfg) == (-1 if cap is None else cap)
     assert B.moe_capacity(B.config_from(synth.CONFIGS[2])) == 2560
-    for cf, k, T, E in [(1.0, 1, 10, 4), (0.5, 2, 1001, 7), (1.25, 2, 16384, 16), (2.0, 1, 5, 8)]:
+    assert B.moe_capacity(B.make_config(20, 64, 64, 4, 1, capacity_factor=1.2)) == 7   # float32(1.2) > 1.2
+    for cf, k, T, E in [(1.0, 1, 10, 4), (0.5, 2, 1001, 7), (1.25, 2, 16384, 16), (2.0, 1, 5, 8),
+                        (1.1, 1, 1000, 10), (1.2, 1, 20, 4), (0.7, 1, 30, 3), (1.3, 2, 12345, 7),
+                        (0.9, 1, 70000, 9), (1.1, 2, 65536, 11)]:
         cfg = B.make_config(T, 64, 64, E, k, capacity_factor=cf)
         assert B.moe_capacity(cfg) == O.capacity(cf, k, T, E)
     # packed-row bound: k*T without capacity; min(k*T, N*min(C, T)) with one
@@ -120,3 +123,12 @@ def test_skew_recipe_of_the_wide_config():
     _, idx, _ = O.gate(inp["x"], inp["Wg_t"].T, inp["bias"], lc.top_k, lc.renorm_topk)
     share = np.bincount(idx.reshape(-1), minlength=lc.E) / idx.size
     assert abs(share[0] - 0.45) < 0.015 and np.all(np.diff(share) < 0)
+
+
+def test_set_option_validates_on_the_host(lib):
+    with pytest.raises(B.MoeError):
+        B.moe_set_option(99, 1)
+    with pytest.raises(B.MoeError):
+        B.moe_set_option(B.MOE_OPT_HANDOVER_SPIN_LIMIT, -1)
+    B.moe_set_option(B.MOE_OPT_HANDOVER_DEVICE_SCOPE, 0)
+    B.moe_set_option(B.MOE_OPT_HANDOVER_SPIN_LIMIT, 1 << 17)

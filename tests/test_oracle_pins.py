@@ -196,6 +196,13 @@ def test_capacity_formula():
     assert O.capacity(1.25, 2, 16384, 16) == 2560
     assert O.capacity(1.0, 1, 10, 4) == 3                 # ceil(2.5)
     assert O.capacity(0.0, 1, 10, 4) is None and O.capacity(-1.0, 2, 10, 4) is None
+    # The factor is a float32 number.  float32(1.2) = 0x3F99999A = 1.2000000476837158203125 exactly,
+    # times 20 / 4 = 6.0000002384185791015625: one more than the 6 a double-precision 1.2 would give.
+    assert O.capacity(1.2, 1, 20, 4) == 7
+    assert O.capacity(np.float32(1.2), 1, 20, 4) == 7
+    assert O.capacity(1.5, 1, 20, 4) == 8                 # 1.5 is exact in float32: 7.5 -> 8
+    # float32(0.7) = 0x3F333333 = 0.699999988079071044921875 < 0.7: 0.7 * 30 / 3 stays at 7
+    assert O.capacity(0.7, 1, 30, 3) == 7
 
 
 def test_all_tokens_to_one_expert_and_empty_experts():
