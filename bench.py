@@ -67,8 +67,9 @@ def cpu_baseline(lc, inp, sample_tokens):
                     capacity_factor=lc.capacity_factor, renorm=lc.renorm_topk)
     dt = time.perf_counter() - t0
     return {"value": xs.shape[0] / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"whole layer (numpy fp64) on the first {xs.shape[0]} of {lc.T} tokens, "
-                      f"all {lc.n_local} local experts' weights, {dt:.2f} s"}
+            "sample": f"whole layer (numpy fp64, its matmuls on the BLAS numpy links, {threads} threads) on "
+                      f"the first {xs.shape[0]} of {lc.T} tokens, all {lc.n_local} local experts' "
+                      f"weights, {dt:.2f} s"}
 
 
 def main():
@@ -94,6 +95,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     B.load_library()
+    B.moe_init()          # one-time set-up of the device (the only call here that synchronises by itself)
     lc = synth.CONFIGS[args.config]
     log(f"[bench] workload {lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
         f"top_k={lc.top_k} cf={lc.capacity_factor} {lc.in_dtype}->{lc.out_dtype}")
@@ -132,6 +134,33 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / K
+    assert B.moe_ffn_check(cfg, ws, True) == 0, "a hand-over of partial sums did not arrive (timed region)"
+
+    # The same K steps replayed from a HIP graph holding one layer call (second reported number:
+    # what a caller that captures the layer pays per step, without the host's launch work).
+    graph_ms_per_step = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+        assert B.moe_ffn_check(cfg, ws, True) == 0, "a hand-over of partial sums did not arrive (graph replays)"
+        del graph
+    except Exception as exc:   # (a failed capture must not cost the run its headline number)
+        log(f"[bench] graph replay not measured: {exc!r}")
 
     # Timed region 2: the same K steps with HIP events recorded on the stream around every stage
     # (each record costs a few microseconds, which is why region 1 carries the headline number).
@@ -140,6 +169,7 @@ def main():
     for i in range(K):
         step(events[i])
     torch.cuda.synchronize()
+    assert B.moe_ffn_check(cfg, ws, True) == 0, "a hand-over of partial sums did not arrive (event region)"
 
     stage_ms = np.zeros(B.MOE_NUM_STAGES)
     for i in range(K):
@@ -242,6 +272,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "graph_ms_per_step": graph_ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": lc.in_dtype, "data": "synthetic",
         "config": {"workload": f"{lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "

@@ -9,8 +9,12 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, row-major and
  *     contiguous.  Only `const moe_config*` and `stage_events` arrays are HOST pointers.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued
- *     asynchronously; nothing here synchronises, allocates or frees device memory.  Results are
- *     valid once the caller has synchronised the stream.
+ *     asynchronously; nothing here allocates or frees device memory.  Results are valid once the
+ *     caller has synchronised the stream.  The calls that SYNCHRONISE the stream are: moe_init;
+ *     moe_ffn_check; moe_event_elapsed_ms (on its event); and, once per device and only if moe_init
+ *     has not been called for that device, the first expert-FFN call (moe_expert_ffn, _up, _down,
+ *     moe_layer_forward, moe_expert_ffn_backward) with bf16/fp16 input -- unless that call is made
+ *     under stream capture, where nothing synchronises (see moe_init).
  *   - Return value: MOE_OK (0) or a negative moe_status.  Arguments are validated on the host
  *     before anything is launched; on error nothing has been enqueued.
  *   - Weights are stored [out, in] (the contraction index is contiguous):
@@ -72,6 +76,29 @@ enum {
   MOE_STAGE_COMBINE = 5,  /* gate-weighted gather into out                         */
   MOE_NUM_STAGES = 6
 };
+
+/* Set-up -------------------------------------------------------------------------------------- */
+
+/* One-time set-up of the CURRENT device for the expert GEMMs: kernel attributes and the placement
+ * check of the persistent blocks (a probe kernel is launched on `stream` and waited for: this call
+ * SYNCHRONISES the stream, so it must not be made under stream capture).  Calling it is optional
+ * but recommended before the first layer call: without it the first expert-FFN call on the device
+ * does the same work, synchronising once; and if that first call is being captured into a graph it
+ * cannot run the check, so it (and every later launch until the check has run outside a capture)
+ * hands partial sums over with device-scope fences, which is correct on any placement but slower.
+ * Idempotent; cheap after the first call. */
+int moe_init(void* stream);
+
+/* Diagnostic switches (process-wide, take effect at the next launch; not needed in normal use).
+ *   MOE_OPT_HANDOVER_DEVICE_SCOPE  value != 0: partial sums of output tiles cut between compute
+ *        units are always handed over with device-scope fences, whatever the placement check found
+ *        (the path a device with another block placement would take); 0: back to automatic.
+ *   MOE_OPT_HANDOVER_SPIN_LIMIT    how many times a compute unit polls for another one's partial
+ *        sums before it gives up and computes the missing part of the tile itself (default 131072;
+ *        0: never wait, always compute it itself).  The output is complete either way.
+ * Returns MOE_ERR_SHAPE for an unknown option or a value outside [0, 2^31). */
+enum { MOE_OPT_HANDOVER_DEVICE_SCOPE = 1, MOE_OPT_HANDOVER_SPIN_LIMIT = 2 };
+int moe_set_option(int option, int64_t value);
 
 /* Host-only helpers ------------------------------------------------------------------------- */
 
@@ -174,12 +201,17 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
 
 /* Health of the expert-FFN calls that used `workspace` since the last check.  When an output tile
  * is cut between compute units, the partial sums are handed over through the workspace with a
- * bounded wait; this call copies the kernel's error word to the host (it SYNCHRONISES the stream)
- * and sets *status (host) to 0: nothing went wrong; 1: a partial sum did not arrive within the
- * wait limit, the affected output tile is incomplete; 2: writer and reader of a partial sum ran on
- * different XCDs although the placement check at set-up said they would not.  A reported error is
- * cleared.  layer_workspace != 0: `workspace` is the one given to moe_layer_forward; 0: the one
- * given to moe_expert_ffn / _up / _down. */
+ * bounded wait.  The persistent kernel expects one block per compute unit to be resident at once,
+ * i.e. the device not to be shared with another stream's kernels while it runs; if a block starts
+ * late, the unit waiting for its partial sums gives up after the spin limit and computes that part
+ * of the tile itself.  The OUTPUT IS COMPLETE AND CORRECT EITHER WAY (only the float32 summation
+ * order of that tile differs from an undisturbed run, and time was lost); this call tells whether
+ * it happened.  It copies the kernel's word to the host (it SYNCHRONISES the stream) and sets
+ * *status (host) to 0: every hand-over went through; 1: at least one partial sum did not arrive
+ * within the spin limit; 2: writer and reader of a partial sum ran on different XCDs although the
+ * placement check at set-up said they would not (the reader then recomputed as in case 1).  A
+ * reported word is cleared.  layer_workspace != 0: `workspace` is the one given to
+ * moe_layer_forward; 0: the one given to moe_expert_ffn / _up / _down. */
 int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
                   int32_t* status, void* stream);
 

@@ -33,6 +33,8 @@ class MoeError(RuntimeError):
 
 _PROTOTYPES = {
     "moe_status_string": (c_char_p, [c_int]),
+    "moe_init": (c_int, [c_void_p]),
+    "moe_set_option": (c_int, [c_int, c_int64]),
     "moe_capacity": (c_int64, [POINTER(MoeConfig)]),
     "moe_max_rows": (c_int64, [POINTER(MoeConfig)]),
     "moe_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
@@ -108,6 +110,18 @@ def config_from(layer_cfg) -> MoeConfig:
     return make_config(layer_cfg.T, layer_cfg.d, layer_cfg.F, layer_cfg.E, layer_cfg.top_k,
                        layer_cfg.local_begin, layer_cfg.n_local, layer_cfg.capacity_factor,
                        layer_cfg.renorm_topk, layer_cfg.in_dtype, layer_cfg.out_dtype)
+
+
+MOE_OPT_HANDOVER_DEVICE_SCOPE, MOE_OPT_HANDOVER_SPIN_LIMIT = 1, 2
+
+
+def moe_init(stream=None):
+    """One-time set-up of the current device (synchronises the stream; not under capture)."""
+    _check(load_library().moe_init(_stream(stream)), "moe_init")
+
+
+def moe_set_option(option: int, value: int):
+    _check(load_library().moe_set_option(int(option), int(value)), "moe_set_option")
 
 
 def moe_capacity(cfg) -> int:

@@ -1,5 +1,7 @@
 // Host side of libppmoe.so: argument validation, workspace layout and the launch sequence of
-// Algorithm 1 (without its closing all-reduce).  Nothing here synchronises or allocates.
+// Algorithm 1 (without its closing all-reduce).  Nothing here allocates; what may synchronise is
+// listed in ppmoe.h (moe_init, moe_ffn_check, moe_event_elapsed_ms, and the first expert-FFN call on
+// a device that moe_init has not prepared).
 
 #include <cmath>
 #include <cstring>
@@ -92,6 +94,24 @@ const char* moe_status_string(int status) {
     case MOE_ERR_WORKSPACE: return "workspace too small";
     case MOE_ERR_HIP: return "a HIP runtime call failed";
     default: return "unknown status";
+  }
+}
+
+int moe_init(void* stream) {
+  return hip_status(grouped_gemm_fast_init(static_cast<hipStream_t>(stream)));
+}
+
+int moe_set_option(int option, int64_t value) {
+  if (value < 0 || value > 0x7fffffff) return MOE_ERR_SHAPE;
+  switch (option) {
+    case MOE_OPT_HANDOVER_DEVICE_SCOPE:
+      grouped_gemm_fast_set_handover(value != 0, -1);
+      return MOE_OK;
+    case MOE_OPT_HANDOVER_SPIN_LIMIT:
+      grouped_gemm_fast_set_handover(-1, static_cast<int>(value));
+      return MOE_OK;
+    default:
+      return MOE_ERR_SHAPE;
   }
 }
 

@@ -89,12 +89,20 @@ inline bool grouped_gemm_can_fuse(int in_dtype, int K, int64_t a_rows) {
 constexpr int kMaxPersistentBlocks = 256;
 size_t grouped_gemm_fast_workspace_bytes();
 // The fast GEMM leaves kGemmErrorMagic | code in one word of its workspace when a hand-over of
-// partial sums went wrong (1: a partial sum did not arrive within the spin limit, 2: writer and
-// reader were not on the same XCD although the set-up check said they would be).
+// partial sums did not take place (1: a partial sum did not arrive within the spin limit, 2: writer
+// and reader were not on the same XCD although the set-up check said they would be); the reading
+// CU then computed the missing part of the tile itself, so the output is complete either way.
 constexpr uint32_t kGemmErrorMagic = 0x4d6f4500u;
 // Copies that word to the host and synchronises the stream.
 hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream_t s);
 inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspace_bytes(); }
+// Per-device set-up of the fast GEMM (kernel attributes, placement check); synchronises `s` once.
+hipError_t grouped_gemm_fast_init(hipStream_t s);
+// Diagnostic switches of the hand-over; a negative value leaves a setting as it is.
+// force_device_scope: 1 = every hand-over uses device-scope fences whatever the placement check said.
+// spin_limit: polls of a flag before the reader gives up and computes the missing k range itself
+// (0 = never wait).
+void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit);
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,

@@ -36,10 +36,16 @@
 // a slot sit on the same XCD, so the hand-over goes through their shared L2 without device-scope
 // cache maintenance (the device-scope fences are kept as a fallback for any other placement).
 //
+// A hand-over that does not arrive within the spin limit (the persistent blocks were not all resident:
+// another kernel held compute units), or that would come from another XCD's L2, is not waited for:
+// the reading CU computes the missing k range itself, so the output tile is always complete and the
+// error word only reports lost time.
+//
 // All LDS traffic is inline assembly with hand-counted lgkmcnt waits, so that the MFMA stream never
-// waits for more than it needs; global loads are plain loads (the compiler counts vmcnt for them).
+// waits for more than it needs; global loads are buffer loads (the compiler counts vmcnt for them).
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -119,10 +125,7 @@ __device__ __forceinline__ int tile_kind(int rows, bool small) {
 // in blocks of row tiles x column tiles (see big_tile_at); then the small tiles, ordered
 // expert-major, then n-tile.
 constexpr int kSmallRows = 128;
-#ifndef PPMOE_MIN_SHARE
-#define PPMOE_MIN_SHARE 16
-#endif
-constexpr int kMinShare = PPMOE_MIN_SHARE;   // k-tiles: the smallest share of a cut stream a CU is given
+constexpr int kMinShare = 16;   // k-tiles: the smallest share of a cut stream a CU is given (8 and 32 measured slower)
 
 __device__ __forceinline__ void expert_tiles(int cnt, int small_rows, int& big_m, int& small) {
   const int m_tiles = (cnt + BM - 1) / BM;
@@ -201,9 +204,12 @@ __device__ __forceinline__ Tile small_tile_at(const int32_t* __restrict__ offset
   return t;
 }
 
-// Scratch for tiles cut between CUs: per block one slot of 256 x 256 float accumulators, one flag.
+// Scratch for tiles cut between CUs: per block one slot of 256 x 256 float accumulators for the
+// partial sums it hands over and one flag, plus a second slot where it parks its own partial sums
+// when a hand-over it waited for did not arrive (the first slot may still be unread by its reader).
 constexpr int kSlotFloats = BM * BN;
-constexpr int kSpinLimit = 1 << 17;   // polls of a flag (a few tenths of a second) before giving up
+constexpr int kSlotsPerBlock = 2;
+constexpr int kDefaultSpinLimit = 1 << 17;   // polls of a flag (a few tenths of a second) before giving up
 
 // The XCD (accelerator complex die) this wavefront runs on.
 __device__ __forceinline__ uint32_t xcc_id() {
@@ -214,8 +220,9 @@ __device__ __forceinline__ uint32_t xcc_id() {
 
 // Set-up check of the placement rule the hand-over of partial sums relies on (block b runs on XCD
 // b mod 8, so blocks b and b' with b = b' mod 8 share an L2): every block reports where it ran.
-__global__ __launch_bounds__(kThreads) void xcc_probe_kernel(uint32_t* __restrict__ out) {
-  if (threadIdx.x == 0) out[blockIdx.x] = xcc_id();
+__device__ uint32_t g_xcc_of_block[kMaxPersistentBlocks];   // (each device holds its own copy)
+__global__ __launch_bounds__(kThreads) void xcc_probe_kernel() {
+  if (threadIdx.x == 0) g_xcc_of_block[blockIdx.x] = xcc_id();
 }
 
 // FUSE: 0: A and C are the packed tensors.  1: the rows of A are read through a list (packed row r is
@@ -227,11 +234,11 @@ template <bool GELU, int FUSE>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
-    uint32_t* __restrict__ flags, uint32_t epoch, int same_l2, const int32_t* __restrict__ aux_rows,
-    const float* __restrict__ aux_w, int aux_div) {
+    uint32_t* __restrict__ flags, uint32_t epoch, int same_l2, int spin_limit,
+    const int32_t* __restrict__ aux_rows, const float* __restrict__ aux_w, int aux_div) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
-  __shared__ int contrib_foreign;
+  __shared__ int contrib_failed;
   const uint32_t my_xcc = xcc_id();
   // A block's flag is down before it can be looked at: whatever the caller's workspace held, a stale
   // word cannot pass for this launch's epoch (the readers poll tens of microseconds from now).
@@ -370,11 +377,23 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   } while (0)
 
 
-  while (round < rounds || u < u_end) {
+  // A hand-over that fails (see below) makes the reader put its own partial sums into its own slot
+  // and run the rest of the tile's k range as one more segment: resume_tl / resume_kb say which.
+  int resume_tl = -1, resume_kb = 0;
+  while (resume_tl >= 0 || round < rounds || u < u_end) {
     // ---- one segment: k-tiles [kb, ke) of one output tile ---------------------------------------
     int tl = 0, kb = 0, ke = KT, kind = 0;
     Tile tc;
-    if (round < rounds) {
+    asm volatile("" : "+s"(resume_tl), "+s"(resume_kb));   // (uniform values: keep them in scalar registers)
+    const bool resumed = resume_tl >= 0;
+    if (resumed) {
+      tl = resume_tl;
+      kb = resume_kb;
+      resume_tl = -1;
+      tc = tl < stream_big ? big_tile_at(offsets, n_exp, n_tiles, small_rows, cus, lx0 + tl)
+                           : small_tile_at(offsets, n_exp, n_tiles, small_rows, sx0 + tl - stream_big);
+      kind = tile_kind(tc.rows, tl >= stream_big);
+    } else if (round < rounds) {
       const int b = round < full_rounds ? (round * 8 + xcd) * cus + cu : lx0 + cu;
       const bool none = round >= full_rounds && b >= lx1;   // the last round may be partial
       ++round;
@@ -549,6 +568,74 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     else if (kind == 2) run_segment(std::integral_constant<int, 2>{});
     else run_segment(std::integral_constant<int, 4>{});
 
+    // A segment that does not hold the first k-tile of its output tile hands its partial sums to the
+    // CU that does (through this block's scratch slot) and raises its flag: mode 1.  The one that
+    // holds it writes the output tile (mode 0), after adding the partial sums of the CUs after it, if
+    // the rest of the k range went there (their first segment, which they finished long ago).  If
+    // those do not arrive it takes nobody's: it parks its own partial sums in its own slot (mode 2,
+    // no flag) and runs the rest of the k range as one more segment, which ends by adding them back.
+    int mode = (kb > 0 && !resumed) ? 1 : 0;
+    int n_contrib = 0;
+    if (resumed) {
+      if (tid == 0) {
+        contrib[0] = 1;
+        contrib[1] = kMaxPersistentBlocks + blockIdx.x;   // its parking slot
+      }
+      __syncthreads();
+      n_contrib = 1;   // (this CU's own stores, complete since the barrier that followed them)
+    } else if (mode == 0 && ke < KT) {
+      if (tid == 0) {
+        // One thread lists the CUs after this one whose share begins inside this tile (skipping empty
+        // shares) and polls their flags (relaxed loads that go to L2, no cache maintenance in the loop).
+        int n = 0, failed = 0;
+        for (int c2 = cu + 1; c2 < cus && share_begin(c2) < static_cast<int64_t>(tl + 1) * KT; ++c2) {
+          if (share_begin(c2 + 1) == share_begin(c2)) continue;
+          const int b2 = (c2 << 3) | xcd;
+          contrib[++n] = b2;
+          int spins = 0;
+          uint32_t f = 0;
+          bool up = false;
+          while (spins < spin_limit) {
+            f = __hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((f >> 4) == epoch) {
+              up = true;
+              break;
+            }
+            ++spins;
+            __builtin_amdgcn_s_sleep(16);
+          }
+          if (!up) {   // not delivered in time (the writer's block may not even be resident yet)
+            failed = 1;
+            flags[kMaxPersistentBlocks] = kGemmErrorMagic | 1u;
+            break;
+          }
+          if (same_l2 && (f & 15u) != my_xcc) {
+            // The partial sums sit in another XCD's L2 and their writer released them at workgroup
+            // scope only (the set-up check of the placement was wrong): they cannot be read safely.
+            failed = 1;
+            flags[kMaxPersistentBlocks] = kGemmErrorMagic | 2u;
+            break;
+          }
+        }
+        contrib[0] = n;
+        contrib_failed = failed;
+      }
+      __syncthreads();
+      if (contrib_failed) {
+        mode = 2;
+      } else {
+        // Once per thread, after the flags are up.  Within an XCD the partial sums are in the shared L2
+        // (stores write through the L1, and this CU has never read these lines since its L1 was
+        // invalidated at the start of the kernel), so ordering against the barrier is all it takes;
+        // the device-scope acquire invalidates the L2, which then misses on every panel being streamed.
+        if (same_l2)
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        else
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        n_contrib = contrib[0];
+      }
+    }
+
     // Per-segment opaque copies: they stop the compiler from hoisting the address arithmetic of the
     // code below out of the segment loop, where it would cost a few hundred live registers.
     uint32_t epi_l = epi;
@@ -558,50 +645,9 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const int row_base = kind ? 0 : wm * 128, col_base = kind ? wave * 64 : wn * 128;
     const int ni_lim = kind ? 2 : 4, wave_cols = kind ? 64 : 128;
 
-    // A segment that does not hold the first k-tile of its output tile hands its partial sums to the
-    // CU that does (through this block's scratch slot); the one that holds it writes the output
-    // tile, after adding the partial sums of the CUs after it, if the rest of the k range went
-    // there (their first segment, which they finished long ago).
-    const bool partial_only = kb > 0;
-    f32x4* my_slot = reinterpret_cast<f32x4*>(slots + static_cast<size_t>(blockIdx.x) * kSlotFloats) + tid_l;
-    int n_contrib = 0;
-    if (!partial_only && ke < KT) {
-      if (tid == 0) {
-        // One thread lists the CUs after this one whose share begins inside this tile (skipping empty
-        // shares) and polls their flags (relaxed loads that go to L2, no cache maintenance in the loop).
-        int n = 0, foreign = 0;
-        for (int c2 = cu + 1; c2 < cus && share_begin(c2) < static_cast<int64_t>(tl + 1) * KT; ++c2) {
-          if (share_begin(c2 + 1) == share_begin(c2)) continue;
-          const int b2 = (c2 << 3) | xcd;
-          contrib[++n] = b2;
-          int spins = 0;
-          uint32_t f;
-          while (((f = __hip_atomic_load(flags + b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 4) != epoch) {
-            if (++spins >= kSpinLimit) {
-              flags[kMaxPersistentBlocks] = kGemmErrorMagic | 1u;   // the result of this tile is incomplete
-              break;
-            }
-            __builtin_amdgcn_s_sleep(16);
-          }
-          if ((f & 15u) != my_xcc) {   // the partial sums sit in another XCD's L2: the set-up check was wrong
-            foreign = 1;
-            flags[kMaxPersistentBlocks] = kGemmErrorMagic | 2u;
-          }
-        }
-        contrib[0] = n;
-        contrib_foreign = foreign;
-      }
-      __syncthreads();
-      // Once per thread, after the flags are up.  Within an XCD the partial sums are in the shared L2
-      // (stores write through the L1, and this CU has never read these lines since its L1 was
-      // invalidated at the start of the kernel), so ordering against the barrier is all it takes;
-      // the device-scope acquire invalidates the L2, which then misses on every panel being streamed.
-      if (same_l2 && !contrib_foreign)
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-      else
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      n_contrib = contrib[0];
-    }
+    int my_slot_id = (mode == 2 ? kMaxPersistentBlocks : 0) + static_cast<int>(blockIdx.x);
+    asm volatile("" : "+s"(my_slot_id));
+    f32x4* my_slot = reinterpret_cast<f32x4*>(slots + static_cast<size_t>(my_slot_id) * kSlotFloats) + tid_l;
 
     // ---- epilogue --------------------------------------------------------------------------------
     // D = W_frag (32 n) x Tok_frag^T (32 m): lane holds token m = lane & 31 and, in register v,
@@ -613,7 +659,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     // they go: that keeps them in the accumulator registers until then.
     __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
     float row_w[4] = {1.f, 1.f, 1.f, 1.f};   // FUSE == 2: gate weight of this lane's row of each row block
-    if (FUSE == 2 && !partial_only) {
+    if (FUSE == 2 && mode == 0) {
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
         const int row = min(row_base + mi * 32 + frow, tc.rows - 1);
@@ -632,7 +678,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
         // Blocks of 32 rows with no valid row are neither sent nor fetched (a 3-row tail tile moves an
         // eighth of a slot).
         const bool live = row_base + mi * 32 < tc.rows && ni < ni_lim;
-        if (partial_only) {
+        if (mode != 0) {
           if (live) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) my_slot[((mi * 4 + ni) * 4 + q) * kThreads] = v[q];
@@ -671,7 +717,16 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
         __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time keeps the register footprint small
       }
     }
-    if (partial_only) {
+    if (mode == 2) {
+      // Parked: the stores are in the L2 once vmcnt is 0 (this CU's L1 holds no line of its own
+      // slot: it has not read it in this launch); the block meets, then goes on with the same tile.
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      resume_tl = tl;
+      resume_kb = ke;
+      continue;
+    }
+    if (mode == 1) {
       // Release: every thread makes its own stores visible device-wide, then the block meets, then
       // one thread raises the flag (a relaxed store is enough after the fences).
       // (Within an XCD: the stores have reached the shared L2 once vmcnt is 0.  The device-scope
@@ -683,12 +738,15 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
       }
       __syncthreads();
-      if (tid == 0)
-        __hip_atomic_store(flags + blockIdx.x, (epoch << 4) | my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) {
+        uint32_t up = (epoch << 4) | my_xcc;
+        asm volatile("" : "+s"(up));   // (formed here: hoisted out of the segment loop it would cost a vector register)
+        __hip_atomic_store(flags + blockIdx.x, up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
       continue;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (n_contrib > 0) {
+    if (n_contrib > 0 && !resumed) {
       // every thread has read the partial sums: lower the flags (the scratch may be reused by a
       // replay of the same launch, whose flags carry the same value)
       __syncthreads();
@@ -747,7 +805,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
 hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream_t s) {
   const float* slots = static_cast<const float*>(workspace);
   const uint32_t* flags = reinterpret_cast<const uint32_t*>(
-      slots + static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats);
+      slots + static_cast<size_t>(fast::kSlotsPerBlock) * kMaxPersistentBlocks * fast::kSlotFloats);
   hipError_t e = hipMemcpyAsync(word, flags + kMaxPersistentBlocks, sizeof(uint32_t),
                                 hipMemcpyDeviceToHost, s);
   if (e != hipSuccess) return e;
@@ -764,9 +822,89 @@ hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream
 }
 
 size_t grouped_gemm_fast_workspace_bytes() {
-  // slots, flags (+1 word), one word per block for the placement check
-  return static_cast<size_t>(kMaxPersistentBlocks) * fast::kSlotFloats * sizeof(float) +
+  // slots, flags (+1 word: the error word)
+  return static_cast<size_t>(fast::kSlotsPerBlock) * kMaxPersistentBlocks * fast::kSlotFloats * sizeof(float) +
          (2 * kMaxPersistentBlocks + 1) * sizeof(uint32_t) + 256;
+}
+
+// ---- per-device set-up --------------------------------------------------------------------------
+// Once per device: the dynamic-LDS attribute of the kernels, the number of persistent blocks, and the
+// placement check (do blocks b and b + 8 share an XCD, as the workgroup-scope hand-over assumes?).
+// The check launches a probe and waits for it, so it is the one thing here that synchronises; it
+// runs from moe_init, or from the first launch on a device that finds it not done -- unless that
+// launch is being captured into a graph, in which case the launch uses device-scope fences and
+// leaves the check for later.
+namespace {
+
+constexpr int kMaxDevices = 64;
+struct FastSetup {
+  bool attrs = false;   // kernel attributes set, `blocks` valid
+  bool probed = false;  // same_l2 valid
+  int blocks = 0;
+  int same_l2 = 0;
+};
+FastSetup g_setup[kMaxDevices];
+std::mutex g_setup_mutex;
+std::atomic<int> g_force_device_scope{0};
+std::atomic<int> g_spin_limit{fast::kDefaultSpinLimit};
+
+hipError_t setup_attrs(FastSetup& st, int dev) {
+  using namespace fast;
+  if (st.attrs) return hipSuccess;
+  const void* kernels[] = {
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2>)};
+  for (const void* k : kernels) {
+    hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+  }
+  int cus = 0;
+  hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
+  st.blocks = cus & ~7;   // one block per CU, the same number on each of the 8 XCDs
+  if (st.blocks < 8) return hipErrorInvalidConfiguration;
+  st.attrs = true;
+  return hipSuccess;
+}
+
+// Launches the placement probe on `s` and waits for it.  Must not be called while `s` is capturing.
+hipError_t setup_probe(FastSetup& st, hipStream_t s) {
+  if (st.probed) return hipSuccess;
+  uint32_t host[kMaxPersistentBlocks];
+  fast::xcc_probe_kernel<<<st.blocks, fast::kThreads, 0, s>>>();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = hipMemcpyFromSymbolAsync(host, HIP_SYMBOL(fast::g_xcc_of_block), st.blocks * sizeof(uint32_t), 0,
+                               hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return e;
+  st.same_l2 = 1;
+  for (int b = 8; b < st.blocks; ++b)
+    if (host[b] != host[b & 7]) st.same_l2 = 0;
+  st.probed = true;
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t grouped_gemm_fast_init(hipStream_t s) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_setup_mutex);
+  e = setup_attrs(g_setup[dev], dev);
+  if (e != hipSuccess) return e;
+  return setup_probe(g_setup[dev], s);
+}
+
+void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit) {
+  if (force_device_scope >= 0) g_force_device_scope = force_device_scope ? 1 : 0;
+  if (spin_limit >= 0) g_spin_limit = spin_limit;
 }
 
 hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
@@ -774,54 +912,39 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
                                     int K, void* workspace, hipStream_t s, int fuse,
                                     const int32_t* aux_rows, const float* aux_w, int aux_div) {
   using namespace fast;
-  struct Setup {
-    hipError_t err;
-    int blocks;
-  };
-  static const Setup setup = [] {
-    Setup r{hipSuccess, 0};
-    const void* kernels[] = {
-        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0>),
-        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0>),
-        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1>),
-        reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2>)};
-    for (const void* k : kernels) {
-      r.err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-      if (r.err != hipSuccess) return r;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  int blocks = 0, same_l2 = 0;
+  {
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    FastSetup& st = g_setup[dev];
+    e = setup_attrs(st, dev);
+    if (e != hipSuccess) return e;
+    if (!st.probed) {
+      hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+      e = hipStreamIsCapturing(s, &cap);
+      if (e != hipSuccess) return e;
+      if (cap == hipStreamCaptureStatusNone) {
+        e = setup_probe(st, s);
+        if (e != hipSuccess) return e;
+      }
     }
-    int dev = 0, cus = 0;
-    r.err = hipGetDevice(&dev);
-    if (r.err != hipSuccess) return r;
-    r.err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (r.err != hipSuccess) return r;
-    if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
-    r.blocks = cus & ~7;   // one block per CU, the same number on each of the 8 XCDs
-    if (r.blocks < 8) r.err = hipErrorInvalidConfiguration;
-    return r;
-  }();
-  if (setup.err != hipSuccess) return setup.err;
+    blocks = st.blocks;
+    same_l2 = st.probed ? st.same_l2 : 0;   // unknown placement: device-scope fences are always right
+  }
+  if (g_force_device_scope.load()) same_l2 = 0;
+  const int spin_limit = g_spin_limit.load();
   static std::atomic<uint32_t> launches{0};
   // 28 bits (the flag word also carries the XCD id), spread over the word so that small integers
   // left in a recycled workspace do not look like an epoch; 0 means "flag down".
   uint32_t epoch = (++launches * 0x9E3779B1u) >> 4;
   if (epoch == 0) epoch = (++launches * 0x9E3779B1u) >> 4;
   float* slots = static_cast<float*>(workspace);
-  uint32_t* flags = reinterpret_cast<uint32_t*>(slots + static_cast<size_t>(kMaxPersistentBlocks) * kSlotFloats);
+  uint32_t* flags = reinterpret_cast<uint32_t*>(
+      slots + static_cast<size_t>(kSlotsPerBlock) * kMaxPersistentBlocks * kSlotFloats);
   (void)max_rows;
-
-  // First launch of the process (it synchronises the stream, once): do blocks b and b + 8 share an
-  // XCD, as the cheap hand-over assumes?  If not, every hand-over uses device-scope fences.
-  static const int same_l2 = [&]() -> int {
-    uint32_t* where = flags + kMaxPersistentBlocks + 1;
-    uint32_t host[kMaxPersistentBlocks];
-    xcc_probe_kernel<<<setup.blocks, kThreads, 0, s>>>(where);
-    if (hipMemcpyAsync(host, where, setup.blocks * sizeof(uint32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
-        hipStreamSynchronize(s) != hipSuccess)
-      return 0;
-    for (int b = 8; b < setup.blocks; ++b)
-      if (host[b] != host[b & 7]) return 0;
-    return 1;
-  }();
   // fuse: 0 none; 1 rows of A through aux_rows (first GEMM only); 2 weighted rows of C placed through
   // aux_rows (second GEMM only)
   if ((fuse == 1 && !gelu) || (fuse == 2 && gelu) || fuse < 0 || fuse > 2 ||
@@ -829,8 +952,8 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
       (fuse == 2 && aux_div != 1))
     return hipErrorInvalidValue;
 #define PPMOE_LAUNCH(G, F)                                                            \
-  grouped_gemm_bf16_fast_kernel<G, F><<<setup.blocks, kThreads, kLdsBytes, s>>>(      \
-      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, aux_rows, aux_w, aux_div)
+  grouped_gemm_bf16_fast_kernel<G, F><<<blocks, kThreads, kLdsBytes, s>>>(            \
+      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, spin_limit, aux_rows, aux_w, aux_div)
   if (fuse == 1) PPMOE_LAUNCH(true, 1);
   else if (fuse == 2) PPMOE_LAUNCH(false, 2);
   else if (gelu) PPMOE_LAUNCH(true, 0);

@@ -226,6 +226,62 @@ def test_expert_ffn_on_oracle_rows(dtype, d, F, counts):
     assert_close(y, y_ref, TOL[dtype], "y_sliced")
 
 
+CUT_TILE_CASES = [
+    (4096, 256, [300, 3, 0, 257]),        # long K: tail tiles go through the cut k-tile stream
+    (256, 4096, [129, 128, 600]),         # long K in the second GEMM
+    (8192, 256, [33, 64, 65, 32]),        # only small tiles, each cut between eight CUs
+    (512, 1024, [1024, 1000, 0, 24]),
+]
+
+
+def run_cut_tile_case(d, F, counts):
+    n = len(counts)
+    A = int(sum(counts))
+    lc = small_cfg(T=A, d=d, F=F, E=n, top_k=1, seed=d + F)
+    inp = synth.make_inputs(lc, parts=("x", "W1_t", "W2_t"))
+    inp["W1_t"] *= 8.0
+    mv = synth.math_views(inp)
+    offsets = ragged_offsets(counts)
+    H_ref, y_ref = O.expert_ffn(inp["x"], offsets, mv["W1"], mv["W2"])
+    dl = DeviceLayer(lc, inp)
+    H, y, status = dl.run_ffn(inp["x"], offsets, want_status=True)
+    assert_close(H, H_ref, TOL["bf16"], "H")
+    assert_close(y, y_ref, TOL["bf16"], "y_sliced")
+    return H, y, status
+
+
+@pytest.mark.parametrize("d,F,counts", CUT_TILE_CASES)
+def test_handover_with_device_scope_fences(d, F, counts):
+    """The hand-over of partial sums as a device with another block placement would do it
+    (device-scope release/acquire instead of the shared-L2 shortcut): same result, bit for bit."""
+    from paper_2304_11414_amd import binding as B
+    H0, y0, st0 = run_cut_tile_case(d, F, counts)
+    B.moe_set_option(B.MOE_OPT_HANDOVER_DEVICE_SCOPE, 1)
+    try:
+        H1, y1, st1 = run_cut_tile_case(d, F, counts)
+    finally:
+        B.moe_set_option(B.MOE_OPT_HANDOVER_DEVICE_SCOPE, 0)
+    assert st0 == 0 and st1 == 0
+    np.testing.assert_array_equal(H0, H1)
+    np.testing.assert_array_equal(y0, y1)
+
+
+@pytest.mark.parametrize("d,F,counts", CUT_TILE_CASES)
+def test_handover_that_never_arrives_is_recomputed(d, F, counts):
+    """Spin limit 0: a compute unit never waits for another one's partial sums and computes the rest
+    of its tile itself.  The output is still complete and within the bar; moe_ffn_check reports that
+    hand-overs were skipped (code 1), once.  Every kernel exits normally."""
+    from paper_2304_11414_amd import binding as B
+    B.moe_set_option(B.MOE_OPT_HANDOVER_SPIN_LIMIT, 0)
+    try:
+        _, _, status = run_cut_tile_case(d, F, counts)
+    finally:
+        B.moe_set_option(B.MOE_OPT_HANDOVER_SPIN_LIMIT, 1 << 17)
+    assert status == 1
+    _, _, status = run_cut_tile_case(d, F, counts)
+    assert status == 0
+
+
 # ------------------------------------------------------------------------------------------ combine
 
 @pytest.mark.parametrize("kw", [
@@ -357,6 +413,65 @@ def test_layer_replays_from_a_hip_graph():
         assert bool((again.view(torch.int16) == eager.view(torch.int16)).all())
 
 
+FIRST_CALL_CAPTURE = r"""
+import sys
+import numpy as np
+import torch
+from paper_2304_11414_amd import binding as B
+from paper_2304_11414_amd import synth
+from paper_2304_11414_amd.synth import LayerConfig
+
+lc = LayerConfig("t", T=1500, d=256, F=4096, E=8, top_k=2, renorm_topk=True, seed=41)
+inp = synth.make_inputs(lc)
+cfg = B.config_from(lc)
+dev = {k: torch.from_numpy(v).cuda().to(torch.bfloat16) for k, v in inp.items() if v is not None}
+ws = torch.empty(B.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+ws.fill_(0x5A)
+out = torch.empty((lc.T, lc.d), dtype=torch.bfloat16, device="cuda")
+side = torch.cuda.Stream()
+torch.cuda.synchronize()
+graph = torch.cuda.CUDAGraph()
+print("capturing the layer as the first library call of the process", flush=True)
+with torch.cuda.stream(side):
+    with torch.cuda.graph(graph, stream=side):
+        B.moe_layer_forward(cfg, dev["x"], dev["Wg_t"], None, dev["W1_t"], dev["W2_t"], out, ws)
+torch.cuda.current_stream().wait_stream(side)
+results = []
+for rep in range(3):
+    out.fill_(3.0)
+    graph.replay()
+    torch.cuda.synchronize()
+    results.append(out.clone())
+    assert B.moe_ffn_check(cfg, ws, True) == 0
+print("replayed; now an eager call (runs the placement check)", flush=True)
+B.moe_init()
+eager = torch.empty_like(out)
+ws2 = torch.empty_like(ws)
+B.moe_layer_forward(cfg, dev["x"], dev["Wg_t"], None, dev["W1_t"], dev["W2_t"], eager, ws2)
+torch.cuda.synchronize()
+assert B.moe_ffn_check(cfg, ws2, True) == 0
+for r in results:
+    assert bool((r.view(torch.int16) == eager.view(torch.int16)).all()), "replay differs from the eager result"
+assert bool(torch.isfinite(eager.float()).all()) and float(eager.float().abs().max()) > 0
+print("FIRST_CALL_CAPTURE_OK", flush=True)
+"""
+
+
+def test_layer_captured_as_the_first_call_of_a_process():
+    """moe_layer_forward under stream capture in a fresh process, before moe_init or any other
+    library call: nothing may synchronise, the capture must stay valid (the placement check is put
+    off and the hand-over uses device-scope fences), and the replays equal a later eager run bit for
+    bit."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-u", "-c", FIRST_CALL_CAPTURE], cwd=root, capture_output=True,
+                       text=True, timeout=300)
+    print(r.stdout, r.stderr, flush=True)
+    assert r.returncode == 0 and "FIRST_CALL_CAPTURE_OK" in r.stdout
+
+
 def test_tensor_parallel_partials_sum_to_the_all_local_output():
     """Emulates the ranks of a tensor-parallel group on one GPU: each call holds a different block of
     experts; the partial outputs (what the all-reduce would sum) add up to the all-local output."""
@@ -376,8 +491,33 @@ def test_tensor_parallel_partials_sum_to_the_all_local_output():
 
 # ------------------------------------------------------------------------------------------ full-size configs
 
-def sampled_rows(info, T, n, seed):
-    """Seeded sample of output rows that covers every class: kept, dropped, not local."""
+def tile_edge_rows(info, seed, max_edges=12):
+    """Packed rows at the seams of the expert GEMMs' tiling, per local expert: its first two and last
+    two rows, and the rows on each side of its 256-row tile edges (all of them for an expert of up to
+    `max_edges` edges, else the first three, the last three and a seeded choice of the others).  The
+    last edge is where the short tail tile, computed by another code path, begins."""
+    rng = np.random.default_rng(1000 + seed)
+    offsets = info["offsets"]
+    per_expert = []
+    for i in range(len(offsets) - 1):
+        lo, hi = int(offsets[i]), int(offsets[i + 1])
+        rows = set()
+        if hi > lo:
+            rows.update(r for r in (lo, lo + 1, hi - 2, hi - 1) if lo <= r < hi)
+            edges = list(range(lo + 256, hi, 256))
+            if len(edges) > max_edges:
+                inner = edges[3:-3]
+                pick = rng.choice(len(inner), size=max_edges - 6, replace=False)
+                edges = edges[:3] + [inner[j] for j in sorted(pick)] + edges[-3:]
+            for m in edges:
+                rows.update((m - 1, m))
+        per_expert.append(np.array(sorted(rows), dtype=np.int64))
+    return per_expert
+
+
+def sampled_rows(info, T, n, seed, k):
+    """Seeded sample of output rows that covers every class (kept, dropped, not local) and the tokens
+    whose packed rows sit at the seams of the GEMM tiling."""
     rng = np.random.default_rng(seed)
     inv = info["inv_perm"]
     kept_any = (inv >= 0).any(axis=1)
@@ -386,11 +526,14 @@ def sampled_rows(info, T, n, seed):
         cand = np.flatnonzero(mask)
         if cand.size:
             rows.update(rng.choice(cand, size=min(8, cand.size), replace=False).tolist())
+    for packed in tile_edge_rows(info, seed):
+        rows.update((info["perm"][packed] // k).tolist())
     return np.array(sorted(rows))
 
 
 @pytest.mark.parametrize("ci,n_rows", [(1, 256), (2, 192), (3, 256), (4, 96), (5, 256)])
 def test_layer_full_size_configs_sampled(ci, n_rows):
+    from paper_2304_11414_amd import binding as B
     lc = synth.CONFIGS[ci]
     print(f"[{lc.name}] drawing inputs", flush=True)
     inp = synth.make_inputs(lc)
@@ -400,7 +543,7 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
     print(f"[{lc.name}] gating + dispatch on the oracle", flush=True)
     _, info = O.layer_forward_rows(np.zeros(0, np.int64), inp["x"], mv["Wg"], inp["bias"], mv["W1"],
                                    mv["W2"], **kw)
-    rows = sampled_rows(info, lc.T, n_rows, seed=ci)
+    rows = sampled_rows(info, lc.T, n_rows, seed=ci, k=lc.top_k)
     print(f"[{lc.name}] oracle on {rows.size} sampled rows", flush=True)
     ref_rows, _ = O.layer_forward_rows(rows, inp["x"], mv["Wg"], inp["bias"], mv["W1"], mv["W2"],
                                        logits_in=info["logits"], **kw)
@@ -428,6 +571,19 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
     assert bool((out[zero_rows] == 0).all())
     assert bool(dl.torch.isfinite(out.float()).all())
     assert max_rel_err(got, ref_rows) < TOL["bf16"]
+    # The intermediates of the two expert GEMMs on the packed rows at the seams of their tiling
+    # (first/last rows of every expert, both sides of every 256-row edge, the short tail tiles).
+    print(f"[{lc.name}] H (and y_sliced) on the tile-edge rows", flush=True)
+    fuses = B.moe_layer_fuses(dl.cfg)
+    for i, packed in enumerate(tile_edge_rows(info, ci)):
+        if packed.size == 0:
+            continue
+        x_sel = inp["x"][info["perm"][packed] // lc.top_k]
+        H_ref, y_ref = O.expert_ffn(x_sel, np.array([0, packed.size]), mv["W1"][i:i + 1], mv["W2"][i:i + 1])
+        sel = dl.torch.from_numpy(packed).cuda()
+        assert_close(to_np(ws["H"][sel]), H_ref, TOL["bf16"], f"{lc.name} H rows of expert {i}")
+        if not fuses & B.MOE_FUSE_COMBINE:
+            assert_close(to_np(ws["y_sliced"][sel]), y_ref, TOL["bf16"], f"{lc.name} y rows of expert {i}")
 
 
 # ---------------------------------------------------------------------------- auxiliary loss
@@ -493,7 +649,7 @@ def test_ffn_check_reads_and_clears_the_error_word():
     ws = torch.empty(B.moe_ffn_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     ws.fill_(0x11)                                   # small integers everywhere: not an error
     assert B.moe_ffn_check(cfg, ws, False) == 0
-    word = (256 * 256 * 256 + 256) * 4               # slots of 256 x 256 floats, then the flags
+    word = (2 * 256 * 256 * 256 + 256) * 4           # two slots of 256 x 256 floats per block, then the flags
     for code in (1, 2):
         ws[word:word + 4] = torch.tensor([code, 0x45, 0x6f, 0x4d], dtype=torch.uint8, device="cuda")
         assert B.moe_ffn_check(cfg, ws, False) == code
