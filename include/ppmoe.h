@@ -171,6 +171,23 @@ int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expe
                        int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                        void* x_sliced, void* workspace, size_t workspace_bytes, void* stream);
 
+/* moe_slice_dispatch for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and kernels as moe_slice_dispatch, but the permutation's per-segment counters live in a fixed
+ * array of MOE_STATIC_SCRATCH_BYTES (4 MiB) of device memory inside the library (one copy on
+ * every device it runs on, held until the process ends) instead of a caller's workspace.  It
+ * allocates and frees nothing.  Limit: moe_dispatch_workspace_bytes(cfg) must not exceed
+ * MOE_STATIC_SCRATCH_BYTES, i.e. (2 * ceil(top_k*T / 64) + 1) * local_count * 4 bytes <= 4 MiB
+ * (top_k*T up to about 4 million assignments with 8 local experts); beyond that the call returns
+ * MOE_ERR_WORKSPACE and launches nothing.  Every call on a device shares that device's array, and
+ * the array keeps the last call's contents (the kernels overwrite every counter they read, nothing
+ * needs clearing): calls that overlap in time on one device -- different streams -- race; order
+ * them on one stream or with events. */
+#define MOE_STATIC_SCRATCH_BYTES (4u << 20)
+int moe_slice_dispatch_static(const moe_config* cfg, const void* x, const int32_t* expert_idx,
+                              int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                              void* x_sliced, void* stream);
+
 /* The row gather of moe_slice_dispatch alone (Algorithm 1: hidden_states.index_select), from index
  * lists already built:  x_sliced[r, :] = x[perm[r] / top_k, :]  for r < offsets[local_count].
  * x [T, d] in_dtype; perm [moe_max_rows] int32 and offsets [local_count + 1] int32 as written by

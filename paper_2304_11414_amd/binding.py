@@ -44,6 +44,7 @@ _PROTOTYPES = {
     "moe_aux_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_aux_loss": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 6 + [c_size_t, c_void_p]),
     "moe_slice_dispatch": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
+    "moe_slice_dispatch_static": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 8),
     "moe_slice_rows": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_ffn_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
@@ -168,6 +169,16 @@ def moe_slice_dispatch(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sl
         byref(cfg), _ptr(x), _ptr(expert_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
         _ptr(inv_perm), _ptr(x_sliced), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream)), "moe_slice_dispatch")
+
+
+MOE_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def moe_slice_dispatch_static(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sliced, stream=None):
+    """moe_slice_dispatch without a workspace argument: nothing is allocated anywhere on the way."""
+    _check(load_library().moe_slice_dispatch_static(
+        byref(cfg), _ptr(x), _ptr(expert_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
+        _ptr(inv_perm), _ptr(x_sliced), _stream(stream)), "moe_slice_dispatch_static")
 
 
 def moe_slice_rows(cfg, x, perm, offsets, x_sliced, stream=None):

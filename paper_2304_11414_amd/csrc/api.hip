@@ -98,6 +98,8 @@ const char* moe_status_string(int status) {
 }
 
 int moe_init(void* stream) {
+  void* scratch = nullptr;
+  if (static_scratch_of_current_device(&scratch) != hipSuccess) return MOE_ERR_HIP;
   return hip_status(grouped_gemm_fast_init(static_cast<hipStream_t>(stream)));
 }
 
@@ -206,6 +208,20 @@ int moe_slice_dispatch(const moe_config* cfg, const void* x, const int32_t* expe
   if (x_sliced != nullptr)
     e = launch_slice(*cfg, x, perm, offsets, x_sliced, max_rows_of(*cfg), s);
   return hip_status(e);
+}
+
+static_assert(kStaticScratchBytes == MOE_STATIC_SCRATCH_BYTES, "header and library disagree");
+
+int moe_slice_dispatch_static(const moe_config* cfg, const void* x, const int32_t* expert_idx,
+                              int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                              void* x_sliced, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (dispatch_scratch_bytes(*cfg) > kStaticScratchBytes) return MOE_ERR_WORKSPACE;
+  void* scratch = nullptr;
+  if (static_scratch_of_current_device(&scratch) != hipSuccess) return MOE_ERR_HIP;
+  return moe_slice_dispatch(cfg, x, expert_idx, counts, offsets, perm, inv_perm, x_sliced, scratch,
+                            kStaticScratchBytes, stream);
 }
 
 int moe_slice_rows(const moe_config* cfg, const void* x, const int32_t* perm, const int32_t* offsets,

@@ -48,6 +48,11 @@ hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* exper
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                           int32_t* seg_scratch, hipStream_t s);
 
+// Allocation-free dispatch: device address of this device's file-scope scratch array of
+// kStaticScratchBytes bytes (looked up on the first call per device, with that device current).
+constexpr size_t kStaticScratchBytes = 4u << 20;
+hipError_t static_scratch_of_current_device(void** ptr);
+
 hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, void* x_sliced, int64_t max_rows, hipStream_t s);
 

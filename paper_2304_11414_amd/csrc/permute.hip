@@ -12,9 +12,40 @@
 // counts/offsets (capacity-clamped, exclusive scan over the local experts) are rebuilt by every
 // wavefront of step 3 from the expert totals, which costs a few shuffles, and written by the first.
 
+#include <mutex>
+
 #include "common.h"
 
 namespace ppmoe {
+
+// Scratch of the allocation-free dispatch call (per-segment counters of the permutation): a
+// file-scope array in device memory, kStaticScratchBytes on every device the library runs on, held
+// until the process ends.  In host code the name below is only a stand-in for the symbol: its device
+// address is looked up once per device (static_scratch_of) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+void* g_scratch_ptr[kMaxScratchDevices] = {};
+std::mutex g_scratch_mutex;
+}  // namespace
+
+hipError_t static_scratch_of_current_device(void** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxScratchDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // (this device's copy: the device is current)
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr int kRegs = kMaxExperts / kWave;  // lane i holds experts i, i+64, i+128, i+192
 
