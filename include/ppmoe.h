@@ -252,6 +252,21 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
                       const void* W1, const void* W2, void* out, void* workspace,
                       size_t workspace_bytes, void* const* stage_events, void* stream);
 
+/* moe_layer_forward that also returns the second value of Algorithm 1, the auxiliary balance loss
+ * (formula and conventions: see moe_aux_loss), without a second pass over the tokens: the gating
+ * kernel adds up the softmax probabilities and the first picks per expert while it scores the tokens
+ * (per block of tokens, in token order) and the permutation's scan launch adds the blocks' sums in
+ * order, so the loss is bitwise reproducible and no [T, E] logits are written.  (float32 input, more
+ * than 64 experts, or a router matrix too large for the LDS: the logits go through the workspace and
+ * the kernels of moe_aux_loss run after the gate.)
+ * l_aux: one float32 in DEVICE memory (4-byte aligned), or NULL for exactly moe_layer_forward;
+ * mean_prob [E] float32 and first_counts [E] int32 in device memory, either may be NULL (both must be
+ * NULL when l_aux is).  Everything else as moe_layer_forward. */
+int moe_layer_forward_aux(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                          const void* W1, const void* W2, void* out, float* l_aux, float* mean_prob,
+                          int32_t* first_counts, void* workspace, size_t workspace_bytes,
+                          void* const* stage_events, void* stream);
+
 /* Which stages moe_layer_forward folds into the expert GEMMs for `cfg` (bf16 input, d a multiple
  * of 64): a mask of
  *   MOE_FUSE_SLICE    the first GEMM reads the token rows through the permutation (Algorithm 1's
@@ -268,6 +283,7 @@ int moe_layer_fuses(const moe_config* cfg);
  * can inspect them after a run.  Any pointer may be NULL. */
 typedef struct {
   size_t expert_idx, gate_w, counts, offsets, perm, inv_perm, x_sliced, H, y_sliced, scratch, gemm;
+  size_t logits, aux;   /* scratch of the balance loss (moe_layer_forward_aux)                   */
 } moe_workspace_layout;
 int moe_workspace_offsets(const moe_config* cfg, moe_workspace_layout* layout);
 

@@ -24,7 +24,8 @@ class MoeConfig(Structure):
 
 class MoeWorkspaceLayout(Structure):
     _fields_ = [(n, c_size_t) for n in ("expert_idx", "gate_w", "counts", "offsets", "perm",
-                                        "inv_perm", "x_sliced", "H", "y_sliced", "scratch", "gemm")]
+                                        "inv_perm", "x_sliced", "H", "y_sliced", "scratch", "gemm",
+                                        "logits", "aux")]
 
 
 class MoeError(RuntimeError):
@@ -53,6 +54,7 @@ _PROTOTYPES = {
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
+    "moe_layer_forward_aux": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 10 + [c_size_t, POINTER(c_void_p), c_void_p]),
     "moe_layer_fuses": (c_int, [POINTER(MoeConfig)]),
     "moe_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
     "moe_mfma_probe": (c_int, [c_int64, c_int, c_void_p, POINTER(c_double), c_void_p]),
@@ -233,6 +235,20 @@ def moe_layer_forward(cfg, x, Wg, bias, W1, W2, out, workspace, stage_events=Non
     _check(load_library().moe_layer_forward(
         byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), ev, _stream(stream)), "moe_layer_forward")
+
+
+def moe_layer_forward_aux(cfg, x, Wg, bias, W1, W2, out, l_aux, mean_prob, first_counts, workspace,
+                          stage_events=None, stream=None):
+    """The layer plus Algorithm 1's second return value (device tensors l_aux[1], mean_prob[E],
+    first_counts[E]; the last two may be None)."""
+    ev = None
+    if stage_events is not None:
+        assert len(stage_events) == MOE_NUM_STAGES + 1
+        ev = (c_void_p * (MOE_NUM_STAGES + 1))(*stage_events)
+    _check(load_library().moe_layer_forward_aux(
+        byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(out), _ptr(l_aux),
+        _ptr(mean_prob), _ptr(first_counts), _ptr(workspace), _nbytes(workspace), ev, _stream(stream)),
+        "moe_layer_forward_aux")
 
 
 MOE_FUSE_SLICE, MOE_FUSE_COMBINE = 1, 2

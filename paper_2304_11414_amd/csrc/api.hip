@@ -49,9 +49,17 @@ int64_t max_rows_of(const moe_config& c) {
 }
 
 size_t dispatch_scratch_bytes(const moe_config& c) {
-  int64_t segs = n_segments(c);
+  int64_t segs = max_segments(c);
   if (segs < 1) segs = 1;
   return static_cast<size_t>(2 * segs + 1) * c.local_count * sizeof(int32_t);
+}
+
+// Scratch of the balance loss inside the layer's workspace: the per-segment partial sums the gating
+// kernel leaves, or what the stand-alone loss kernels need, whichever is larger.
+size_t aux_region_bytes(const moe_config& c) {
+  const size_t fused = static_cast<size_t>(max_segments(c)) * c.E * (sizeof(float) + sizeof(int32_t));
+  const size_t alone = aux_scratch_bytes(c);
+  return fused > alone ? fused : alone;
 }
 
 void layout_of(const moe_config& c, moe_workspace_layout* L, size_t* total) {
@@ -75,6 +83,8 @@ void layout_of(const moe_config& c, moe_workspace_layout* L, size_t* total) {
   L->H = take(rows * c.F * eb);
   L->y_sliced = take(rows * c.d * eb);
   L->gemm = take(grouped_gemm_workspace_bytes());
+  L->logits = take(tk / c.top_k * c.E * 4);
+  L->aux = take(aux_region_bytes(c));
   *total = off;
 }
 
@@ -328,16 +338,19 @@ int moe_layer_fuses(const moe_config* cfg) {
   return layer_fuses(*cfg);
 }
 
-int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
-                      const void* W1, const void* W2, void* out, void* workspace,
-                      size_t workspace_bytes, void* const* stage_events, void* stream) {
+int moe_layer_forward_aux(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                          const void* W1, const void* W2, void* out, float* l_aux, float* mean_prob,
+                          int32_t* first_counts, void* workspace, size_t workspace_bytes,
+                          void* const* stage_events, void* stream) {
   int st = check_config(cfg);
   if (st != MOE_OK) return st;
   if (x == nullptr || Wg == nullptr || W1 == nullptr || W2 == nullptr || out == nullptr ||
       workspace == nullptr)
     return MOE_ERR_NULL;
+  if (l_aux == nullptr && (mean_prob != nullptr || first_counts != nullptr)) return MOE_ERR_NULL;
   if (misaligned(x) || misaligned(Wg) || misaligned(bias) || misaligned(W1) || misaligned(W2) ||
-      misaligned(out) || misaligned(workspace))
+      misaligned(out) || misaligned(workspace) || misaligned(mean_prob) || misaligned(first_counts) ||
+      (reinterpret_cast<uintptr_t>(l_aux) & 3u) != 0)
     return MOE_ERR_ALIGN;
   moe_workspace_layout L;
   size_t total = 0;
@@ -356,6 +369,8 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
   int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
   int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
   int32_t* inv_perm = reinterpret_cast<int32_t*>(ws + L.inv_perm);
+  int32_t* seg_scratch = reinterpret_cast<int32_t*>(ws + L.scratch);
+  float* logits = reinterpret_cast<float*>(ws + L.logits);
   void* x_sliced = ws + L.x_sliced;
   void* H = ws + L.H;
   void* y_sliced = ws + L.y_sliced;
@@ -372,11 +387,32 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
     if (e != hipSuccess) return MOE_ERR_HIP; \
   } while (0)
 
+  // Gating.  Where the router runs in the kernel that holds Wg in LDS, that kernel also counts the
+  // picks per segment of the permutation (one launch less below) and, when the balance loss is
+  // wanted, leaves its partial sums; the permutation's scan launch then finishes the loss.
+  const bool want_aux = l_aux != nullptr;
+  const bool fused_gate = gate_is_fused_kernel(c);
+  GateFusion fusion = {};
+  if (fused_gate) {
+    fusion.seg_count = seg_scratch;
+    if (want_aux) {
+      fusion.part_prob = reinterpret_cast<float*>(ws + L.aux);
+      fusion.part_cnt = reinterpret_cast<int32_t*>(fusion.part_prob + static_cast<size_t>(max_segments(c)) * c.E);
+    }
+  }
   PPMOE_TRY(mark(MOE_STAGE_GATE));
-  PPMOE_TRY(launch_gate(c, x, Wg, bias, nullptr, nullptr, expert_idx, gate_w, s));
+  PPMOE_TRY(launch_gate(c, x, Wg, bias, nullptr, (want_aux && !fused_gate) ? logits : nullptr, expert_idx,
+                        gate_w, s, fused_gate ? &fusion : nullptr));
   PPMOE_TRY(mark(MOE_STAGE_PERMUTE));
-  PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm,
-                           reinterpret_cast<int32_t*>(ws + L.scratch), s));
+  if (fusion.seg_assign > 0) {
+    const AuxOut aux = {l_aux, mean_prob, first_counts, fusion.part_prob, fusion.part_cnt, fusion.n_seg, c.E, c.T};
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s,
+                             fusion.seg_assign, true, want_aux ? &aux : nullptr));
+  } else {
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s));
+    if (want_aux)
+      PPMOE_TRY(launch_aux_loss(c, logits, expert_idx, l_aux, mean_prob, first_counts, ws + L.aux, s));
+  }
   // (a stage folded into a GEMM is empty; its events are still recorded)
   const int fuses = layer_fuses(c);
   PPMOE_TRY(mark(MOE_STAGE_SLICE));
@@ -405,6 +441,13 @@ int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, cons
   PPMOE_TRY(mark(MOE_NUM_STAGES));
 #undef PPMOE_TRY
   return MOE_OK;
+}
+
+int moe_layer_forward(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                      const void* W1, const void* W2, void* out, void* workspace,
+                      size_t workspace_bytes, void* const* stage_events, void* stream) {
+  return moe_layer_forward_aux(cfg, x, Wg, bias, W1, W2, out, nullptr, nullptr, nullptr, workspace,
+                               workspace_bytes, stage_events, stream);
 }
 
 int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {

@@ -11,7 +11,8 @@ namespace ppmoe {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxExperts = 256;   // E limit of the ABI
 constexpr int kMaxTopK = 8;
-constexpr int kSegment = 64;       // assignments ranked by one wavefront in the permutation
+constexpr int kSegment = 64;       // assignments per segment of the permutation when it counts them itself
+constexpr int kGateTokens = 16;    // tokens one wavefront of the bf16 gating kernel scores at a time
 
 typedef uint16_t bf16_t;           // raw bf16 bits in memory
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte piece
@@ -38,15 +39,42 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// Where the balance loss (Algorithm 1's l_aux) goes, and the per-segment partial sums it is made of:
+// part_prob / part_cnt [n_part, E] (sum of the softmax probabilities and number of first picks per
+// expert over the tokens of a segment).  l_aux == nullptr: no loss wanted.
+struct AuxOut {
+  float* l_aux;
+  float* mean_prob;        // [E] or nullptr
+  int32_t* first_counts;   // [E] or nullptr
+  const float* part_prob;
+  const int32_t* part_cnt;
+  int n_part, E, T;
+};
+
+// What the fused gating kernel can do on the way (launch_gate, bf16 only): count the picks per
+// permutation segment, and leave the partial sums of the balance loss.
+struct GateFusion {
+  int32_t* seg_count;   // [local_count, n_seg] or nullptr
+  float* part_prob;     // [n_seg, E] or nullptr
+  int32_t* part_cnt;    // [n_seg, E] or nullptr
+  int seg_assign;       // out: assignments per segment the kernel used (0: it did not take this path)
+  int n_seg;            // out
+};
+
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
                        const float* logits_in, float* logits_out, int32_t* expert_idx,
-                       float* gate_w, hipStream_t s);
+                       float* gate_w, hipStream_t s, GateFusion* fusion = nullptr);
+// Does launch_gate take the kernel that can honour a GateFusion request for this configuration?
+bool gate_is_fused_kernel(const moe_config& c);
 
-// seg_scratch: int32[(local_count) * n_segments * 2 + local_count] device scratch.
+// seg_scratch: int32[local_count * max_segments * 2 + local_count] device scratch.
+// seg_assign: consecutive assignments per segment; counted: seg_scratch already holds the
+// per-segment counts (written by the gating kernel); aux: see AuxOut (may be nullptr).
 hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* expert_idx,
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
-                          int32_t* seg_scratch, hipStream_t s);
+                          int32_t* seg_scratch, hipStream_t s, int seg_assign = kSegment,
+                          bool counted = false, const AuxOut* aux = nullptr);
 
 // Allocation-free dispatch: device address of this device's file-scope scratch array of
 // kStaticScratchBytes bytes (looked up on the first call per device, with that device current).
@@ -113,9 +141,13 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
                                     int K, void* workspace, hipStream_t s, int fuse,
                                     const int32_t* aux_rows, const float* aux_w, int aux_div);
 
-inline int64_t n_segments(const moe_config& c) {
-  int64_t a = static_cast<int64_t>(c.T) * c.top_k;
-  return (a + kSegment - 1) / kSegment;
+// Most segments the permutation can be asked for: kSegment assignments each when it counts them
+// itself, the tokens of one wavefront of the gating kernel each when that kernel counts them.
+inline int64_t max_segments(const moe_config& c) {
+  const int64_t a = static_cast<int64_t>(c.T) * c.top_k;
+  const int64_t by_assign = (a + kSegment - 1) / kSegment;
+  const int64_t by_tokens = (static_cast<int64_t>(c.T) + kGateTokens - 1) / kGateTokens;
+  return by_assign > by_tokens ? by_assign : by_tokens;
 }
 
 }  // namespace ppmoe

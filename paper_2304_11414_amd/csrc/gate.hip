@@ -16,7 +16,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 // order.  Picks are found without a "taken" mask: the next pick is the largest element that comes
 // strictly after the previous pick in that order.
 __device__ __forceinline__ void softmax_topk_row(const float* lg, int E, int k, int renorm,
-                                                 int32_t* idx_out, float* w_out) {
+                                                 int32_t* idx_out, float* w_out,
+                                                 int32_t* idx_copy = nullptr, float* max_out = nullptr,
+                                                 float* sum_out = nullptr) {
   float m = lg[0];
   for (int e = 1; e < E; ++e) m = fmaxf(m, lg[e]);
   float sum = 0.f;
@@ -37,6 +39,7 @@ __device__ __forceinline__ void softmax_topk_row(const float* lg, int E, int k, 
     }
     float w = expf(bv - m) / sum;
     idx_out[j] = best;
+    if (idx_copy != nullptr) idx_copy[j] = best;
     w_out[j] = w;
     wsum += w;
     pv = bv;
@@ -44,6 +47,137 @@ __device__ __forceinline__ void softmax_topk_row(const float* lg, int E, int k, 
   }
   if (renorm) {
     for (int j = 0; j < k; ++j) w_out[j] = w_out[j] / wsum;
+  }
+  if (max_out != nullptr) *max_out = m;
+  if (sum_out != nullptr) *sum_out = sum;
+}
+
+// The same routine for a row of at most EP logits sitting in LDS: they are read into registers in
+// one go (the loops above would pay one LDS latency per element) and every loop is unrolled over EP
+// with the elements past E switched off.  Same arithmetic in the same order as softmax_topk_row:
+// the two give the same bits.  On return the row holds the logits still, or, if probs_out, the
+// softmax probabilities.
+template <int EP>
+__device__ __forceinline__ void softmax_topk_row_regs(float* lg, const float* __restrict__ bias,
+                                                      float* __restrict__ logits_out, int E, int k,
+                                                      int renorm, int32_t* idx_out, float* w_out,
+                                                      int32_t* idx_copy, bool probs_out) {
+  float v[EP];
+#pragma unroll
+  for (int e = 0; e < EP; ++e) v[e] = lg[e];
+  if (bias != nullptr) {
+#pragma unroll
+    for (int e = 0; e < EP; ++e)
+      if (e < E) v[e] += bias[e];
+  }
+  if (logits_out != nullptr) {
+#pragma unroll
+    for (int e = 0; e < EP; ++e)
+      if (e < E) logits_out[e] = v[e];
+  }
+  float m = v[0];
+#pragma unroll
+  for (int e = 1; e < EP; ++e)
+    if (e < E) m = fmaxf(m, v[e]);
+  float p[EP];
+  float sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < EP; ++e)
+    if (e < E) {
+      p[e] = expf(v[e] - m);
+      sum += p[e];
+    }
+  float pv = __builtin_inff();
+  int pe = -1;
+  float wsum = 0.f;
+  for (int j = 0; j < k; ++j) {
+    int best = -1;
+    float bv = 0.f, bp = 0.f;
+#pragma unroll
+    for (int e = 0; e < EP; ++e) {
+      const bool after_prev = (v[e] < pv) || (v[e] == pv && e > pe);
+      if (e < E && after_prev && (best < 0 || v[e] > bv)) {
+        best = e;
+        bv = v[e];
+        bp = p[e];
+      }
+    }
+    const float w = bp / sum;
+    idx_out[j] = best;
+    if (idx_copy != nullptr) idx_copy[j] = best;
+    w_out[j] = w;
+    wsum += w;
+    pv = bv;
+    pe = best;
+  }
+  if (renorm) {
+    for (int j = 0; j < k; ++j) w_out[j] = w_out[j] / wsum;
+  }
+  if (probs_out) {
+#pragma unroll
+    for (int e = 0; e < EP; ++e)
+      if (e < E) lg[e] = p[e] / sum;
+  }
+}
+
+// What a block adds once it has scored its tokens (one segment of the permutation that follows):
+// its picks per local expert (seg_count), and the sums of the softmax probabilities and of the first
+// picks per expert (part_prob, part_cnt: partial sums of the balance loss).  One thread per expert
+// walks the block's tokens in order, so everything is bitwise reproducible.
+// tile[tok * ld + e]: probabilities (zeros for tokens past T); picks[tok * k + j]: picks (-1 past T).
+__device__ __forceinline__ void block_segment_sums(const float* tile, int ld, const int32_t* picks,
+                                                   int n_tok, int k, int E, int local_begin,
+                                                   int n_local, int seg, int n_seg,
+                                                   int32_t* __restrict__ seg_count,
+                                                   float* __restrict__ part_prob,
+                                                   int32_t* __restrict__ part_cnt) {
+  for (int e = threadIdx.x; e < max(E, n_local); e += blockDim.x) {
+    if (seg_count != nullptr && e < n_local) {
+      int cnt = 0;
+      for (int a = 0; a < n_tok * k; ++a) cnt += picks[a] == local_begin + e;
+      seg_count[static_cast<size_t>(e) * n_seg + seg] = cnt;
+    }
+    if (part_prob != nullptr && e < E) {
+      float p = 0.f;
+      int first = 0;
+      for (int tok = 0; tok < n_tok; ++tok) {
+        p += tile[tok * ld + e];
+        first += picks[tok * k] == e;
+      }
+      part_prob[static_cast<size_t>(seg) * E + e] = p;
+      part_cnt[static_cast<size_t>(seg) * E + e] = first;
+    }
+  }
+}
+
+// One token's share of the tail: softmax + top-k on its row of the logits tile, outputs, and what
+// block_segment_sums needs.
+template <int EP>
+__device__ __forceinline__ void score_token(float* lg, int t, int T, int E, int k, int renorm,
+                                            const float* __restrict__ bias,
+                                            float* __restrict__ logits_out,
+                                            int32_t* __restrict__ expert_idx,
+                                            float* __restrict__ gate_w, int32_t* pk, bool extras,
+                                            bool probs) {
+  if (t < T) {
+    float* lo = logits_out != nullptr ? logits_out + static_cast<size_t>(t) * E : nullptr;
+    if constexpr (EP > 0) {
+      softmax_topk_row_regs<EP>(lg, bias, lo, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
+                                gate_w + static_cast<size_t>(t) * k, extras ? pk : nullptr, probs);
+    } else {
+      if (bias != nullptr)
+        for (int e = 0; e < E; ++e) lg[e] += bias[e];
+      if (lo != nullptr)
+        for (int e = 0; e < E; ++e) lo[e] = lg[e];
+      float m, sum;
+      softmax_topk_row(lg, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
+                       gate_w + static_cast<size_t>(t) * k, extras ? pk : nullptr, &m, &sum);
+      if (probs)
+        for (int e = 0; e < E; ++e) lg[e] = expf(lg[e] - m) / sum;
+    }
+  } else if (extras) {
+    for (int j = 0; j < k; ++j) pk[j] = -1;
+    for (int e = 0; e < E; ++e) lg[e] = 0.f;
   }
 }
 
@@ -56,10 +190,13 @@ template <int NT, int MT>
 __global__ __launch_bounds__(256) void gate_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg, const float* __restrict__ bias,
     float* __restrict__ logits_out, int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
-    int T, int d, int E, int k, int renorm) {
+    int32_t* __restrict__ seg_count, float* __restrict__ part_prob, int32_t* __restrict__ part_cnt,
+    int T, int d, int E, int k, int renorm, int local_begin, int n_local) {
   constexpr int kTok = 16 * MT;
   constexpr int kLd = NT * 16 + 1;
   __shared__ float red[kTok * kLd];
+  __shared__ int32_t picks[kTok * kMaxTopK];
+  const bool extras = seg_count != nullptr || part_prob != nullptr;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 15, g = lane >> 4;
@@ -131,17 +268,15 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(
     __syncthreads();
   }
 
-  if (threadIdx.x < kTok) {
-    int t = t0 + threadIdx.x;
-    if (t < T) {
-      float* lg = &red[threadIdx.x * kLd];
-      if (bias != nullptr)
-        for (int e = 0; e < E; ++e) lg[e] += bias[e];
-      if (logits_out != nullptr)
-        for (int e = 0; e < E; ++e) logits_out[static_cast<size_t>(t) * E + e] = lg[e];
-      softmax_topk_row(lg, E, k, renorm, expert_idx + static_cast<size_t>(t) * k,
-                       gate_w + static_cast<size_t>(t) * k);
-    }
+  // The tail: one thread per token (rows of up to 64 experts go through registers).
+  if (threadIdx.x < kTok)
+    score_token<(NT <= 4 ? NT * 16 : 0)>(&red[threadIdx.x * kLd], t0 + threadIdx.x, T, E, k, renorm, bias,
+                                         logits_out, expert_idx, gate_w, picks + threadIdx.x * k, extras,
+                                         part_prob != nullptr);
+  if (extras) {   // the block's tokens are one segment of the permutation that follows
+    __syncthreads();
+    block_segment_sums(red, kLd, picks, kTok, k, E, local_begin, n_local, blockIdx.x, gridDim.x,
+                       seg_count, part_prob, part_cnt);
   }
 }
 
@@ -203,37 +338,46 @@ __global__ __launch_bounds__(256) void gate_from_logits_kernel(
 
 template <int NT, int MT>
 static void launch_bf16(const moe_config& c, const void* x, const void* Wg, const float* bias,
-                        float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s) {
+                        float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s,
+                        GateFusion* fusion) {
   int blocks = (c.T + 16 * MT - 1) / (16 * MT);
   gate_bf16_kernel<NT, MT><<<blocks, 256, 0, s>>>(
       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(Wg), bias, logits_out, expert_idx,
-      gate_w, c.T, c.d, c.E, c.top_k, c.renorm_topk);
+      gate_w, fusion != nullptr ? fusion->seg_count : nullptr,
+      fusion != nullptr ? fusion->part_prob : nullptr, fusion != nullptr ? fusion->part_cnt : nullptr,
+      c.T, c.d, c.E, c.top_k, c.renorm_topk, c.local_begin, c.local_count);
+  if (fusion != nullptr) {
+    fusion->seg_assign = 16 * MT * c.top_k;
+    fusion->n_seg = blocks;
+  }
 }
+
+// Can launch_gate honour a GateFusion request for this configuration?  (Every bf16 router kernel can.)
+bool gate_is_fused_kernel(const moe_config& c) { return c.in_dtype == MOE_BF16 && c.T > 0; }
 
 hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
                        const float* logits_in, float* logits_out, int32_t* expert_idx,
-                       float* gate_w, hipStream_t s) {
+                       float* gate_w, hipStream_t s, GateFusion* fusion) {
+  if (fusion != nullptr) fusion->seg_assign = fusion->n_seg = 0;
   if (c.T == 0) return hipSuccess;
   if (logits_in != nullptr) {
     gate_from_logits_kernel<<<(c.T + 255) / 256, 256, 0, s>>>(logits_in, logits_out, expert_idx,
                                                               gate_w, c.T, c.E, c.top_k,
                                                               c.renorm_topk);
-  } else if (c.in_dtype == MOE_F32) {
+    return hipGetLastError();
+  }
+  if (c.in_dtype == MOE_F32) {
     gate_f32_kernel<<<(c.T + 3) / 4, 256, 0, s>>>(static_cast<const float*>(x),
                                                   static_cast<const float*>(Wg), bias, logits_out,
                                                   expert_idx, gate_w, c.T, c.d, c.E, c.top_k,
                                                   c.renorm_topk);
-  } else if (c.E <= 16) {
-    launch_bf16<1, 1>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
-  } else if (c.E <= 32) {
-    launch_bf16<2, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
-  } else if (c.E <= 64) {
-    launch_bf16<4, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
-  } else if (c.E <= 128) {
-    launch_bf16<8, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
-  } else {
-    launch_bf16<16, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s);
+    return hipGetLastError();
   }
+  if (c.E <= 16) launch_bf16<1, 1>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  else if (c.E <= 32) launch_bf16<2, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  else if (c.E <= 64) launch_bf16<4, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  else if (c.E <= 128) launch_bf16<8, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  else launch_bf16<16, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
   return hipGetLastError();
 }
 

@@ -4,8 +4,10 @@
 // The position of assignment a = t*k + j in its expert's queue is the number of earlier assignments
 // to the same expert.  It is computed without order-dependent atomics, so the permutation is
 // identical on every run and on every rank of a tensor-parallel group:
-//   1. every wavefront owns a segment of kSegment consecutive assignments and counts, per local
-//      expert, how many of them it holds (ballot + popcount, counts kept in registers);
+//   1. every wavefront owns a segment of seg_assign consecutive assignments (64 when this file counts
+//      them; the tokens of one block when the gating kernel has already counted them on the way)
+//      and counts, per local expert, how many of them it holds (ballot + popcount, counts kept in
+//      registers);
 //   2. one wavefront per expert turns the per-segment counts into exclusive prefix sums;
 //   3. every wavefront walks its segment again, 64 assignments at a time: rank inside the step by
 //      ballot/popcount, plus the running count carried in registers, plus the segment's prefix.
@@ -70,14 +72,15 @@ __device__ __forceinline__ void add_slot(int (&run)[kRegs], int e, int amount) {
 // expert i.
 __device__ __forceinline__ void count_segment(const int32_t* __restrict__ expert_idx,
                                               int32_t* seg_count, int seg, int64_t n_assign,
-                                              int n_seg, int local_begin, int n_local) {
+                                              int n_seg, int seg_assign, int local_begin, int n_local) {
   const int lane = lane_id();
   int run[kRegs] = {0, 0, 0, 0};
-  const int64_t base = static_cast<int64_t>(seg) * kSegment;
-  for (int step = 0; step < kSegment / kWave; ++step) {
+  const int64_t base = static_cast<int64_t>(seg) * seg_assign;
+  const int64_t end = min(n_assign, base + seg_assign);
+  for (int step = 0; step * kWave < seg_assign; ++step) {
     int64_t a = base + step * kWave + lane;
     int e = -1;
-    if (a < n_assign) {
+    if (a < end) {
       unsigned le = static_cast<unsigned>(expert_idx[a] - local_begin);
       if (le < static_cast<unsigned>(n_local)) e = static_cast<int>(le);
     }
@@ -100,9 +103,11 @@ __device__ __forceinline__ void count_segment(const int32_t* __restrict__ expert
 __global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __restrict__ expert_idx,
                                                             int32_t* __restrict__ seg_count,
                                                             int64_t n_assign, int n_seg,
-                                                            int local_begin, int n_local) {
+                                                            int seg_assign, int local_begin,
+                                                            int n_local) {
   const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (seg < n_seg) count_segment(expert_idx, seg_count, seg, n_assign, n_seg, local_begin, n_local);
+  if (seg < n_seg)
+    count_segment(expert_idx, seg_count, seg, n_assign, n_seg, seg_assign, local_begin, n_local);
 }
 
 // Step 2.  One wavefront per local expert: seg_base = exclusive scan of seg_count over segments
@@ -128,18 +133,45 @@ __device__ __forceinline__ void scan_expert(const int32_t* seg_count, int32_t* s
   if (lane == 0) totals[i] = carry;
 }
 
+// Blocks 0 .. n_local-1 scan one expert each.  One more block, when the gating kernel has left
+// per-segment partial sums for the balance loss (Algorithm 1's l_aux; see aux.hip for the formula),
+// adds them up in segment order (fixed order: bitwise reproducible) and writes the loss.
 __global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
                                                           int32_t* __restrict__ seg_base,
-                                                          int32_t* __restrict__ totals, int n_seg) {
-  scan_expert(seg_count, seg_base, totals, blockIdx.x, n_seg);
+                                                          int32_t* __restrict__ totals, int n_seg,
+                                                          int n_local, AuxOut aux) {
+  if (static_cast<int>(blockIdx.x) < n_local) {
+    scan_expert(seg_count, seg_base, totals, blockIdx.x, n_seg);
+    return;
+  }
+  __shared__ float term[kMaxExperts];
+  const int lane = lane_id();
+  for (int e = lane; e < aux.E; e += kWave) {
+    float prob = 0.f;
+    int cnt = 0;
+    for (int g = 0; g < aux.n_part; ++g) {
+      prob += aux.part_prob[static_cast<size_t>(g) * aux.E + e];
+      cnt += aux.part_cnt[static_cast<size_t>(g) * aux.E + e];
+    }
+    const float mp = aux.T > 0 ? prob / static_cast<float>(aux.T) : 0.f;
+    if (aux.mean_prob != nullptr) aux.mean_prob[e] = mp;
+    if (aux.first_counts != nullptr) aux.first_counts[e] = cnt;
+    term[e] = aux.T > 0 ? mp * (static_cast<float>(cnt) / static_cast<float>(aux.T)) : 0.f;
+  }
+  __syncthreads();
+  if (lane == 0) {
+    float sum = 0.f;
+    for (int e = 0; e < aux.E; ++e) sum += term[e];   // ascending expert order
+    *aux.l_aux = static_cast<float>(aux.E) * sum;
+  }
 }
 
 // Step 3.
 __device__ __forceinline__ void rank_segment(
     const int32_t* __restrict__ expert_idx, const int32_t* seg_base, const int32_t* totals,
     int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
-    int32_t* __restrict__ inv_perm, int seg, int64_t n_assign, int n_seg, int local_begin,
-    int n_local, int cap /* INT_MAX when unlimited */) {
+    int32_t* __restrict__ inv_perm, int seg, int64_t n_assign, int n_seg, int seg_assign,
+    int local_begin, int n_local, int cap /* INT_MAX when unlimited */) {
   const int lane = lane_id();
 
   // Kept queue lengths and their exclusive scan over the local experts (ascending expert id).
@@ -165,11 +197,12 @@ __device__ __forceinline__ void rank_segment(
   }
   if (seg == 0 && lane == 0) offsets[n_local] = carry;
 
-  const int64_t base = static_cast<int64_t>(seg) * kSegment;
-  for (int step = 0; step < kSegment / kWave; ++step) {
+  const int64_t base = static_cast<int64_t>(seg) * seg_assign;
+  const int64_t end = min(n_assign, base + seg_assign);
+  for (int step = 0; step * kWave < seg_assign; ++step) {
     int64_t a = base + step * kWave + lane;
     int e = -1;
-    if (a < n_assign) {
+    if (a < end) {
       unsigned le = static_cast<unsigned>(expert_idx[a] - local_begin);
       if (le < static_cast<unsigned>(n_local)) e = static_cast<int>(le);
     }
@@ -189,7 +222,7 @@ __device__ __forceinline__ void rank_segment(
       add_slot(run, e0, __popcll(same));
       todo &= ~same;
     }
-    if (a < n_assign) {
+    if (a < end) {
       inv_perm[a] = row;
       if (row >= 0) perm[row] = static_cast<int32_t>(a);
     }
@@ -200,35 +233,39 @@ __global__ __launch_bounds__(256) void rank_kernel(
     const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ seg_base,
     const int32_t* __restrict__ totals, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int64_t n_assign, int n_seg,
-    int local_begin, int n_local, int cap) {
+    int seg_assign, int local_begin, int n_local, int cap) {
   const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (seg < n_seg)
     rank_segment(expert_idx, seg_base, totals, counts, offsets, perm, inv_perm, seg, n_assign, n_seg,
-                 local_begin, n_local, cap);
+                 seg_assign, local_begin, n_local, cap);
 }
 
 hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* expert_idx,
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
-                          int32_t* seg_scratch, hipStream_t s) {
+                          int32_t* seg_scratch, hipStream_t s, int seg_assign, bool counted,
+                          const AuxOut* aux) {
   const int64_t n_assign = static_cast<int64_t>(c.T) * c.top_k;
-  const int n_seg = static_cast<int>(n_segments(c));
+  const int n_seg = static_cast<int>((n_assign + seg_assign - 1) / seg_assign);
   const int N = c.local_count;
   int32_t* seg_count = seg_scratch;
   int32_t* seg_base = seg_scratch + static_cast<int64_t>(N) * n_seg;
   int32_t* totals = seg_base + static_cast<int64_t>(N) * n_seg;
   const int cap_i = (cap < 0 || cap > 0x7fffffff) ? 0x7fffffff : static_cast<int>(cap);
   const int blocks = n_seg > 0 ? (n_seg + 3) / 4 : 0;
-  if (blocks > 0)
-    segment_count_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_count, n_assign, n_seg,
+  if (blocks > 0 && !counted)
+    segment_count_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_count, n_assign, n_seg, seg_assign,
                                                 c.local_begin, N);
-  segment_scan_kernel<<<N, 64, 0, s>>>(seg_count, seg_base, totals, n_seg);
+  AuxOut no_aux = {};
+  const bool with_aux = aux != nullptr && aux->l_aux != nullptr;
+  segment_scan_kernel<<<N + (with_aux ? 1 : 0), 64, 0, s>>>(seg_count, seg_base, totals, n_seg, N,
+                                                            with_aux ? *aux : no_aux);
   if (blocks > 0) {
     rank_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_base, totals, counts, offsets, perm,
-                                       inv_perm, n_assign, n_seg, c.local_begin, N, cap_i);
+                                       inv_perm, n_assign, n_seg, seg_assign, c.local_begin, N, cap_i);
   } else {
     // T == 0: counts and offsets are still defined (all zero); one wavefront writes them.
     rank_kernel<<<1, 64, 0, s>>>(expert_idx, seg_base, totals, counts, offsets, perm, inv_perm, 0, 1,
-                                 c.local_begin, N, cap_i);
+                                 seg_assign, c.local_begin, N, cap_i);
   }
   return hipGetLastError();
 }

@@ -145,12 +145,24 @@ class DeviceLayer:
         t.cuda.synchronize()
         return to_np(out)
 
-    def run_layer(self, ws_fill=0xAB):
+    def run_layer(self, ws_fill=0xAB, aux=False):
+        """One fused layer call.  aux=True: through moe_layer_forward_aux; the views then also hold
+        l_aux (float), mean_prob [E] and first_counts [E] as NumPy arrays."""
         t, c = self.torch, self.cfg
         ws = self.workspace(fill=ws_fill)
         out = self.empty((c.T, c.d), torch_dtype(self.lc.out_dtype))
         out.fill_(7.0)
-        B.moe_layer_forward(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, ws)
-        assert B.moe_ffn_check(c, ws, True) == 0, "a hand-over of partial sums failed"
+        if aux:
+            l_aux = t.full((1,), -1.0, dtype=t.float32, device="cuda")
+            mean_prob = t.full((c.E,), -1.0, dtype=t.float32, device="cuda")
+            first = t.full((c.E,), -1, dtype=t.int32, device="cuda")
+            B.moe_layer_forward_aux(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, l_aux, mean_prob,
+                                    first, ws)
+        else:
+            B.moe_layer_forward(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, ws)
+        assert B.moe_ffn_check(c, ws, True) == 0, "a hand-over of partial sums did not arrive"
         t.cuda.synchronize()
-        return out, B.workspace_views(c, ws)
+        views = B.workspace_views(c, ws)
+        if aux:
+            views.update(l_aux=float(l_aux.item()), mean_prob=to_np(mean_prob), first_counts=to_np(first))
+        return out, views

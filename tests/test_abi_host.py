@@ -74,7 +74,8 @@ def test_workspace_layout_is_disjoint_and_aligned(lib):
         sizes = dict(scratch=B.moe_dispatch_workspace_bytes(cfg), expert_idx=tk * 4, gate_w=tk * 4,
                      counts=lc.n_local * 4, offsets=(lc.n_local + 1) * 4, perm=rows * 4,
                      inv_perm=tk * 4, x_sliced=rows * lc.d * eb, H=rows * lc.F * eb,
-                     y_sliced=rows * lc.d * eb, gemm=B.moe_ffn_workspace_bytes(cfg))
+                     y_sliced=rows * lc.d * eb, gemm=B.moe_ffn_workspace_bytes(cfg),
+                     logits=lc.T * lc.E * 4, aux=B.moe_aux_workspace_bytes(cfg))
         spans = sorted((getattr(L, n), getattr(L, n) + s) for n, s in sizes.items())
         for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
             assert a1 <= b0

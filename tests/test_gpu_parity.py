@@ -312,13 +312,25 @@ def test_combine_on_oracle_rows(kw):
 
 # ------------------------------------------------------------------------------------------ whole layer
 
+AUX_TOL = 2e-5   # float32 sums over T tokens of probabilities that rest on float32 logits
+
+
+def check_aux(ws, ref_logits, ref_idx, what):
+    """l_aux, mean_prob, first_counts of moe_layer_forward_aux against the oracle on its own logits."""
+    ref = O.aux_loss(ref_logits, ref_idx)
+    np.testing.assert_array_equal(ws["first_counts"], ref["first_counts"])
+    assert_close(ws["mean_prob"], ref["mean_prob"], AUX_TOL, f"{what} mean_prob")
+    assert abs(ws["l_aux"] - ref["l_aux"]) <= AUX_TOL * abs(ref["l_aux"]), (what, ws["l_aux"], ref["l_aux"])
+
+
 def compare_layer_full(lc, inp):
     mv = synth.math_views(inp)
     ref = O.layer_forward(inp["x"], mv["Wg"], inp["bias"], mv["W1"], mv["W2"], E=lc.E, k=lc.top_k,
                           local_begin=lc.local_begin, local_count=lc.n_local,
                           capacity_factor=lc.capacity_factor, renorm=lc.renorm_topk)
     dl = DeviceLayer(lc, inp)
-    out, ws = dl.run_layer()
+    out, ws = dl.run_layer(aux=True)
+    check_aux(ws, ref["logits"], ref["expert_idx"], lc.name)
     exact = O.router_logits(inp["x"], mv["Wg"], inp["bias"])
     margin = pick_margin(exact, lc.top_k).min() if lc.T else np.inf
     assert margin > 5e-6, f"seed gives a near-tie (margin {margin:.2e}); pick another seed"
@@ -549,7 +561,11 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
                                        logits_in=info["logits"], **kw)
     print(f"[{lc.name}] GPU layer", flush=True)
     dl = DeviceLayer(lc, inp)
-    out, ws = dl.run_layer()
+    out, ws = dl.run_layer(aux=True)
+    check_aux(ws, info["logits"], info["expert_idx"], lc.name)
+    plain, _ = dl.run_layer()                        # the call without the loss gives the same output bits
+    assert bool((plain.view(dl.torch.uint8) == out.view(dl.torch.uint8)).all())
+    del plain
     exact = O.router_logits(inp["x"], mv["Wg"], inp["bias"])
     gpu_idx = to_np(ws["expert_idx"])
     differ = np.flatnonzero((gpu_idx != info["expert_idx"]).any(axis=1))
