@@ -219,9 +219,23 @@ def main():
     xs = torch.empty((rows_max, lc.d), dtype=tdt, device="cuda")
     ys = torch.empty((rows_max, lc.d), dtype=tdt, device="cuda").normal_()
     out2 = torch.empty_like(out)
+    def timed_graph(fn, reps=20):
+        """Mean time of one call, `reps` calls replayed from a HIP graph (kernel time without the
+        host's launch gaps, which are a sixth of a 12 us kernel)."""
+        fn(None)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(reps):
+                    fn(side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return timed(g.replay, 3) / reps
     standalone_ms = {
-        "slice": timed(lambda: B.moe_slice_rows(cfg, dev["x"], views["perm"], views["offsets"], xs), 20),
-        "combine": timed(lambda: B.moe_combine(cfg, ys, views["inv_perm"], views["gate_w"], out2), 20)}
+        "slice": timed_graph(lambda st: B.moe_slice_rows(cfg, dev["x"], views["perm"], views["offsets"], xs, stream=st)),
+        "combine": timed_graph(lambda st: B.moe_combine(cfg, ys, views["inv_perm"], views["gate_w"], out2, stream=st))}
     del xs, ys, out2
 
     counts = views["counts"].cpu().numpy()
