@@ -20,9 +20,10 @@
  *   - Weights are stored [out, in] (the contraction index is contiguous):
  *     Wg[E, d], W1[N, F, d] (the paper's A_i transposed), W2[N, d, F] (B_i transposed).
  *   - in_dtype is the type of x, Wg, W1, W2, x_sliced, H, y_sliced; out_dtype the type of `out`.
- *     Supported pairs: (F32, F32), (BF16, BF16), (BF16, F32).  Logits, softmax and gate weights are
- *     always float32 (the paper keeps the gating module in float32, Section 4.1); GEMMs accumulate
- *     in float32.
+ *     Supported pairs: (F32, F32), (BF16, BF16), (BF16, F32), (F16, F16), (F16, F32) -- F16 is IEEE
+ *     half precision, the paper's own training precision (Section 4.1).  Logits, softmax and gate
+ *     weights are always float32 (the paper keeps the gating module in float32, Section 4.1); GEMMs
+ *     accumulate in float32 and round to nearest even when they store a 16-bit type.
  *   - Shapes: T >= 0 tokens, d and F multiples of 8, 1 <= top_k <= E <= 256, top_k <= 8,
  *     0 <= local_begin, local_begin + local_count <= E, local_count >= 1, k*T < 2^31.
  *   - Inputs are assumed finite.  With NaN logits the pick order is unspecified.
@@ -47,7 +48,7 @@ typedef enum {
   MOE_ERR_HIP = -6        /* a HIP runtime call (launch, event record) failed        */
 } moe_status;
 
-typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1, MOE_F16 = 2 } moe_dtype;
 
 /* Problem statement of one MoE layer on one device (Sections 3.3.1-3.3.3):
  * T = b*s token embeddings of size d = h, E experts in the tensor-parallel group of which this

@@ -11,7 +11,7 @@ from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_float, c_int
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libppmoe.so")
 
-MOE_F32, MOE_BF16 = 0, 1
+MOE_F32, MOE_BF16, MOE_F16 = 0, 1, 2
 MOE_NUM_STAGES = 6
 STAGE_NAMES = ("gate", "permute", "slice", "ffn_up", "ffn_down", "combine")
 
@@ -103,7 +103,7 @@ def _stream(stream):
 
 def make_config(T, d, F, E, top_k, local_begin=0, local_count=None, capacity_factor=0.0,
                 renorm_topk=False, in_dtype="bf16", out_dtype="bf16") -> MoeConfig:
-    code = {"f32": MOE_F32, "bf16": MOE_BF16}
+    code = {"f32": MOE_F32, "bf16": MOE_BF16, "f16": MOE_F16}
     return MoeConfig(T, d, F, E, top_k, local_begin, E if local_count in (None, -1) else local_count,
                      float(capacity_factor), int(bool(renorm_topk)), code[in_dtype], code[out_dtype])
 
@@ -300,8 +300,8 @@ def workspace_views(cfg, workspace):
     tk = cfg.T * cfg.top_k
     rows = moe_max_rows(cfg)
     n = cfg.local_count
-    et = torch.bfloat16 if cfg.in_dtype == MOE_BF16 else torch.float32
-    eb = 2 if cfg.in_dtype == MOE_BF16 else 4
+    et = {MOE_BF16: torch.bfloat16, MOE_F16: torch.float16, MOE_F32: torch.float32}[cfg.in_dtype]
+    eb = 4 if cfg.in_dtype == MOE_F32 else 2
 
     def view(off, count, dtype, size):
         return workspace[off:off + count * size].view(dtype)

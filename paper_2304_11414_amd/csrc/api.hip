@@ -15,7 +15,7 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-inline size_t elem_bytes(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+inline size_t elem_bytes(int dtype) { return is_16bit(dtype) ? 2 : 4; }
 
 int check_config(const moe_config* c) {
   if (c == nullptr) return MOE_ERR_NULL;
@@ -26,7 +26,7 @@ int check_config(const moe_config* c) {
     return MOE_ERR_SHAPE;
   if (static_cast<int64_t>(c->T) * c->top_k >= (1ll << 31)) return MOE_ERR_SHAPE;
   const bool ok = (c->in_dtype == MOE_F32 && c->out_dtype == MOE_F32) ||
-                  (c->in_dtype == MOE_BF16 && (c->out_dtype == MOE_BF16 || c->out_dtype == MOE_F32));
+                  (is_16bit(c->in_dtype) && (c->out_dtype == c->in_dtype || c->out_dtype == MOE_F32));
   if (!ok) return MOE_ERR_DTYPE;
   if (!(c->capacity_factor == c->capacity_factor)) return MOE_ERR_SHAPE;  // NaN
   return MOE_OK;
@@ -328,7 +328,7 @@ int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_
 static int layer_fuses(const moe_config& c) {
   if (!grouped_gemm_can_fuse(c.in_dtype, c.d, c.T)) return 0;
   int f = MOE_FUSE_SLICE;
-  if (c.top_k == 1 && c.out_dtype == MOE_BF16 && grouped_gemm_is_fast(c.in_dtype, c.F))
+  if (c.top_k == 1 && c.out_dtype == c.in_dtype && grouped_gemm_is_fast(c.in_dtype, c.F))
     f |= MOE_FUSE_COMBINE;
   return f;
 }

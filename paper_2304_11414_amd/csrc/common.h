@@ -61,6 +61,57 @@ struct GateFusion {
   int n_seg;            // out
 };
 
+// The two 16-bit element types (MOE_BF16, MOE_F16; the paper trains in fp16, Section 4.1): what the
+// matrix instructions and the conversions look like for each.  Both are raw 16-bit words in memory.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+template <int DT>
+struct Elem16;
+template <>
+struct Elem16<MOE_BF16> {
+  typedef bf16x8 vec8;
+  static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
+  static __device__ __forceinline__ float widen(uint16_t b) { return bf16_to_f32(b); }
+  // the two halves of a 32-bit word holding two elements (lo in bits 0..15)
+  static __device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xffff0000u);
+  }
+};
+template <>
+struct Elem16<MOE_F16> {
+  typedef f16x8 vec8;
+  static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+  // round to nearest even (the default rounding mode of the conversion)
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+  }
+  static __device__ __forceinline__ float widen(uint16_t b) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, b));
+  }
+  static __device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi) {
+    const f16x2_t v = __builtin_bit_cast(f16x2_t, w);
+    lo = static_cast<float>(v.x);
+    hi = static_cast<float>(v.y);
+  }
+};
+inline bool is_16bit(int dtype) { return dtype == MOE_BF16 || dtype == MOE_F16; }
+
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
                        const float* logits_in, float* logits_out, int32_t* expert_idx,
@@ -111,7 +162,7 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
                                const int32_t* aux_rows = nullptr, const float* aux_w = nullptr,
                                int aux_div = 1);
 inline bool grouped_gemm_is_fast(int in_dtype, int K) {
-  return in_dtype == MOE_BF16 && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
+  return is_16bit(in_dtype) && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
 }
 // Can A be read through a row list?  Its byte offsets must fit the 32-bit offsets of the loads.
 inline bool grouped_gemm_can_fuse(int in_dtype, int K, int64_t a_rows) {
@@ -136,7 +187,7 @@ hipError_t grouped_gemm_fast_init(hipStream_t s);
 // spin_limit: polls of a flag before the reader gives up and computes the missing k range itself
 // (0 = never wait).
 void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit);
-hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
+hipError_t launch_grouped_gemm_fast(int in_dtype, bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
                                     const int32_t* aux_rows, const float* aux_w, int aux_div);

@@ -10,7 +10,6 @@
 
 namespace ppmoe {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 
 // One token: softmax over all E logits, then k picks in descending (logit, then ascending index)
 // order.  Picks are found without a "taken" mask: the next pick is the largest element that comes
@@ -186,7 +185,7 @@ __device__ __forceinline__ void score_token(float* lg, int t, int T, int E, int 
 // fixed.  MFMA operands come straight from global memory: lane (r = lane%16, g = lane/16) holds 8
 // consecutive k of row r, which is exactly a 16-byte load; four such loads cover 64 contiguous
 // bytes of each of the 16 rows.
-template <int NT, int MT>
+template <int NT, int MT, int DT>
 __global__ __launch_bounds__(256) void gate_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg, const float* __restrict__ bias,
     float* __restrict__ logits_out, int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
@@ -247,9 +246,9 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, a[u][mt][i]), __builtin_bit_cast(bf16x8, b[u][nt][i]),
-                acc[mt][nt], 0, 0, 0);
+            acc[mt][nt] = Elem16<DT>::mfma16(__builtin_bit_cast(typename Elem16<DT>::vec8, a[u][mt][i]),
+                                             __builtin_bit_cast(typename Elem16<DT>::vec8, b[u][nt][i]),
+                                             acc[mt][nt]);
   }
 
   // D layout of the 16x16 MFMA: lane holds column (lane % 16), rows (lane / 16) * 4 + i.
@@ -341,19 +340,23 @@ static void launch_bf16(const moe_config& c, const void* x, const void* Wg, cons
                         float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s,
                         GateFusion* fusion) {
   int blocks = (c.T + 16 * MT - 1) / (16 * MT);
-  gate_bf16_kernel<NT, MT><<<blocks, 256, 0, s>>>(
-      static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(Wg), bias, logits_out, expert_idx,
-      gate_w, fusion != nullptr ? fusion->seg_count : nullptr,
-      fusion != nullptr ? fusion->part_prob : nullptr, fusion != nullptr ? fusion->part_cnt : nullptr,
-      c.T, c.d, c.E, c.top_k, c.renorm_topk, c.local_begin, c.local_count);
+#define PPMOE_GATE(DT)                                                                                 \
+  gate_bf16_kernel<NT, MT, DT><<<blocks, 256, 0, s>>>(                                                 \
+      static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(Wg), bias, logits_out, expert_idx,     \
+      gate_w, fusion != nullptr ? fusion->seg_count : nullptr,                                         \
+      fusion != nullptr ? fusion->part_prob : nullptr, fusion != nullptr ? fusion->part_cnt : nullptr, \
+      c.T, c.d, c.E, c.top_k, c.renorm_topk, c.local_begin, c.local_count)
+  if (c.in_dtype == MOE_F16) PPMOE_GATE(MOE_F16);
+  else PPMOE_GATE(MOE_BF16);
+#undef PPMOE_GATE
   if (fusion != nullptr) {
     fusion->seg_assign = 16 * MT * c.top_k;
     fusion->n_seg = blocks;
   }
 }
 
-// Can launch_gate honour a GateFusion request for this configuration?  (Every bf16 router kernel can.)
-bool gate_is_fused_kernel(const moe_config& c) { return c.in_dtype == MOE_BF16 && c.T > 0; }
+// Can launch_gate honour a GateFusion request for this configuration?  (The 16-bit router kernel can.)
+bool gate_is_fused_kernel(const moe_config& c) { return is_16bit(c.in_dtype) && c.T > 0; }
 
 hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const float* bias,
                        const float* logits_in, float* logits_out, int32_t* expert_idx,

@@ -20,8 +20,6 @@
 
 namespace ppmoe {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 __device__ __forceinline__ float gelu_tanh_fast(float u) {
   // 0.5 u (1 + tanh(z)) = u / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3)
@@ -95,7 +93,7 @@ constexpr int kTileBytes = kBM * kBK * 2;  // one operand tile in LDS: 32 KiB
 // XOR-swizzled with the row number.
 __device__ __forceinline__ int lds_piece(int row, int ch) { return row * 128 + ((ch ^ ((row >> 1) & 7)) << 4); }
 
-template <bool GELU>
+template <bool GELU, int DT>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K) {
@@ -171,18 +169,19 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
     const unsigned char* base = lds + stage * (2 * kTileBytes);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 tok[4], wgt[2];
+      typedef typename Elem16<DT>::vec8 vec8;
+      vec8 tok[4], wgt[2];
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
-        tok[mi] = *reinterpret_cast<const bf16x8*>(base + tok_base + mi * (32 * 128) + piece[ks]);
+        tok[mi] = *reinterpret_cast<const vec8*>(base + tok_base + mi * (32 * 128) + piece[ks]);
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        wgt[ni] = *reinterpret_cast<const bf16x8*>(base + wgt_base + ni * (32 * 128) + piece[ks]);
+        wgt[ni] = *reinterpret_cast<const vec8*>(base + wgt_base + ni * (32 * 128) + piece[ks]);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt[ni], tok[mi], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = Elem16<DT>::mfma32(wgt[ni], tok[mi], acc[mi][ni]);
     }
     if (kt + 1 < KT) store_lds(stage ^ 1);
     __syncthreads();
@@ -211,8 +210,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
           v3 = gelu_tanh_fast(v3);
         }
         uint2 p;
-        p.x = pack_bf16x2(v0, v1);
-        p.y = pack_bf16x2(v2, v3);
+        p.x = Elem16<DT>::pack2(v0, v1);
+        p.y = Elem16<DT>::pack2(v2, v3);
         *reinterpret_cast<uint2*>(crow + n) = p;
       }
     }
@@ -293,11 +292,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 
 static hipError_t ensure_lds_attr() {
   static hipError_t done = [] {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kTileBytes);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kTileBytes);
+    const void* kernels[] = {reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<true, MOE_BF16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<false, MOE_BF16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<true, MOE_F16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<false, MOE_F16>)};
+    for (const void* k : kernels) {
+      hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kTileBytes);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }();
   return done;
 }
@@ -308,12 +311,12 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
                                const float* aux_w, int aux_div) {
   if (max_rows == 0) return hipSuccess;
   if (grouped_gemm_is_fast(in_dtype, K)) {
-    return launch_grouped_gemm_fast(gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
+    return launch_grouped_gemm_fast(in_dtype, gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
                                     static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s,
                                     fuse, aux_rows, aux_w, aux_div);
   }
   if (fuse != 0) return hipErrorInvalidValue;   // the other kernels work on packed tensors only
-  if (in_dtype == MOE_BF16) {
+  if (is_16bit(in_dtype)) {
     hipError_t e = ensure_lds_attr();
     if (e != hipSuccess) return e;
     const int64_t m_tiles = (max_rows + kBM - 1) / kBM + n_exp;   // upper bound on sum of ceilings
@@ -322,12 +325,17 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
     const bf16_t* a = static_cast<const bf16_t*>(A);
     const bf16_t* b = static_cast<const bf16_t*>(B);
     bf16_t* c = static_cast<bf16_t*>(C);
-    if (gelu)
-      grouped_gemm_bf16_kernel<true><<<static_cast<unsigned>(grid), kGemmThreads, 4 * kTileBytes, s>>>(
-          a, b, c, offsets, n_exp, Nout, K);
-    else
-      grouped_gemm_bf16_kernel<false><<<static_cast<unsigned>(grid), kGemmThreads, 4 * kTileBytes, s>>>(
-          a, b, c, offsets, n_exp, Nout, K);
+#define PPMOE_GEMM16(G, DT)                                                                         \
+  grouped_gemm_bf16_kernel<G, DT><<<static_cast<unsigned>(grid), kGemmThreads, 4 * kTileBytes, s>>>( \
+      a, b, c, offsets, n_exp, Nout, K)
+    if (in_dtype == MOE_F16) {
+      if (gelu) PPMOE_GEMM16(true, MOE_F16);
+      else PPMOE_GEMM16(false, MOE_F16);
+    } else {
+      if (gelu) PPMOE_GEMM16(true, MOE_BF16);
+      else PPMOE_GEMM16(false, MOE_BF16);
+    }
+#undef PPMOE_GEMM16
   } else {
     const int64_t m_tiles = (max_rows + kFM - 1) / kFM + n_exp;
     const int64_t n_tiles = (Nout + kFN - 1) / kFN;

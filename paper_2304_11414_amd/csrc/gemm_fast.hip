@@ -52,8 +52,6 @@
 
 namespace ppmoe {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace fast {
 
@@ -96,8 +94,8 @@ __device__ __forceinline__ f32x4 gelu_tanh4(f32x4 u) {
   return u * r;
 }
 
-template <int OFF>
-__device__ __forceinline__ void lds_read16(bf16x8& dst, uint32_t addr) {
+template <int OFF, typename V>
+__device__ __forceinline__ void lds_read16(V& dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
 }
 template <int OFF>
@@ -230,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void xcc_probe_kernel() {
 // the loads of the first GEMM.  2: packed row r of the result is multiplied by aux_w[aux_rows[r]] and stored
 // as row aux_rows[r] of C: the placement of the expert outputs into the layer output done by the
 // stores of the second GEMM (top-1 only: a row of C is then written by at most one packed row).
-template <bool GELU, int FUSE>
+template <bool GELU, int FUSE, int DT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
@@ -310,7 +308,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   do {                                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
     if (KIND == 0 || (mi < KIND && ni < 2))                                                          \
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[4 + ni], f[mi], acc[mi][ni], 0, 0, 0); \
+      acc[mi][ni] = Elem16<DT>::mfma32(f[4 + ni], f[mi], acc[mi][ni]);                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define PPMOE_READ_TOK(f, i, ks, buf)                                                  \
@@ -483,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
             const_cast<unsigned char*>(gbase), 0, t <= last ? n_records : 0, 0x00020000);
         stage[set * 16 + n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[n], t * (BK * 2), 0);
       };
-      bf16x8 f0[8], f1[8];
+      typename Elem16<DT>::vec8 f0[8], f1[8];
       // Small tile: every wavefront reads the token rows from row 0 and its own 64 weight rows.
       // (the shifts are made opaque so that the shifted addresses are computed here, per segment, and
       // not once per kind before the segment loop, where they would be live across everything)
@@ -710,7 +708,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
             if (FUSE == 2) w *= row_w[mi];
             const int chunk = ni * 4 + q;   // 16-byte chunk of the 256-byte row; `half` picks its 8-byte half
             const uint32_t a = epi_l + r * 256 + ((chunk ^ (r & 15)) << 4) + half * 8;
-            const uint32_t lo = pack_bf16x2(w[0], w[1]), hi = pack_bf16x2(w[2], w[3]);
+            const uint32_t lo = Elem16<DT>::pack2(w[0], w[1]), hi = Elem16<DT>::pack2(w[2], w[3]);
             asm volatile("ds_write_b64 %0, %1" : : "v"(a), "v"(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32)) : "memory");
           }
         }
@@ -852,10 +850,14 @@ hipError_t setup_attrs(FastSetup& st, int dev) {
   using namespace fast;
   if (st.attrs) return hipSuccess;
   const void* kernels[] = {
-      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0>),
-      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0>),
-      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1>),
-      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2>)};
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0, MOE_BF16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0, MOE_BF16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1, MOE_BF16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2, MOE_BF16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 0, MOE_F16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 0, MOE_F16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<true, 1, MOE_F16>),
+      reinterpret_cast<const void*>(grouped_gemm_bf16_fast_kernel<false, 2, MOE_F16>)};
   for (const void* k : kernels) {
     hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
@@ -907,7 +909,7 @@ void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit) {
   if (spin_limit >= 0) g_spin_limit = spin_limit;
 }
 
-hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
+hipError_t launch_grouped_gemm_fast(int in_dtype, bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
                                     const int32_t* aux_rows, const float* aux_w, int aux_div) {
@@ -951,13 +953,19 @@ hipError_t launch_grouped_gemm_fast(bool gelu, const bf16_t* A, const bf16_t* B,
       (fuse != 0 && aux_rows == nullptr) || (fuse == 2 && aux_w == nullptr) || aux_div < 1 ||
       (fuse == 2 && aux_div != 1))
     return hipErrorInvalidValue;
-#define PPMOE_LAUNCH(G, F)                                                            \
-  grouped_gemm_bf16_fast_kernel<G, F><<<blocks, kThreads, kLdsBytes, s>>>(            \
+#define PPMOE_LAUNCH_DT(G, F, DT)                                                     \
+  grouped_gemm_bf16_fast_kernel<G, F, DT><<<blocks, kThreads, kLdsBytes, s>>>(        \
       A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, spin_limit, aux_rows, aux_w, aux_div)
+#define PPMOE_LAUNCH(G, F)                            \
+  do {                                                \
+    if (in_dtype == MOE_F16) PPMOE_LAUNCH_DT(G, F, MOE_F16); \
+    else PPMOE_LAUNCH_DT(G, F, MOE_BF16);             \
+  } while (0)
   if (fuse == 1) PPMOE_LAUNCH(true, 1);
   else if (fuse == 2) PPMOE_LAUNCH(false, 2);
   else if (gelu) PPMOE_LAUNCH(true, 0);
   else PPMOE_LAUNCH(false, 0);
+#undef PPMOE_LAUNCH_DT
 #undef PPMOE_LAUNCH
   return hipGetLastError();
 }

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kCopyThreads) void slice_rows_kernel(
 hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, void* x_sliced, int64_t max_rows, hipStream_t s) {
   if (max_rows == 0 || c.T == 0) return hipSuccess;
-  const int elem = c.in_dtype == MOE_BF16 ? 2 : 4;
+  const int elem = is_16bit(c.in_dtype) ? 2 : 4;
   const int chunks_per_row = c.d * elem / 16;
   int64_t want = (max_rows + kRowsPerIter - 1) / kRowsPerIter;
   int blocks = static_cast<int>(want < 256 * kSliceBlocksPerCu ? want : 256 * kSliceBlocksPerCu);
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kCopyThreads) void zero_unrouted_rows_kernel(
 hipError_t launch_zero_unrouted_rows(const moe_config& c, const int32_t* inv_perm, void* out,
                                      hipStream_t s) {
   if (c.T == 0) return hipSuccess;
-  const int elem = c.out_dtype == MOE_BF16 ? 2 : 4;
+  const int elem = is_16bit(c.out_dtype) ? 2 : 4;
   const int blocks = c.T < 256 * 16 ? c.T : 256 * 16;
   zero_unrouted_rows_kernel<<<blocks, kCopyThreads, 0, s>>>(inv_perm, static_cast<u32x4*>(out), c.T,
                                                             c.d * elem / 16);
@@ -119,32 +119,28 @@ hipError_t launch_copy_bytes(const void* src, void* dst, int64_t bytes, hipStrea
 // type; it reads the matching n elements of y: 16 bytes, or 8 when bf16 is combined into float32.
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename TIn, int N>
+// DIN / DOUT: moe_dtype of y_sliced and of out.
+template <int DIN, int N>
 struct Piece;
-template <>
-struct Piece<bf16_t, 8> {
+template <int DIN>
+struct Piece<DIN, 8> {   // eight 16-bit elements
   typedef u32x4 type;
   __device__ static void widen(const u32x4& v, float* f) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(w[i] << 16);
-      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
+    for (int i = 0; i < 4; ++i) Elem16<DIN>::widen2(w[i], f[2 * i], f[2 * i + 1]);
   }
 };
-template <>
-struct Piece<bf16_t, 4> {
+template <int DIN>
+struct Piece<DIN, 4> {   // four 16-bit elements
   typedef u32x2 type;
   __device__ static void widen(const u32x2& v, float* f) {
-    f[0] = __uint_as_float(v.x << 16);
-    f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16);
-    f[3] = __uint_as_float(v.y & 0xffff0000u);
+    Elem16<DIN>::widen2(v.x, f[0], f[1]);
+    Elem16<DIN>::widen2(v.y, f[2], f[3]);
   }
 };
 template <>
-struct Piece<float, 4> {
+struct Piece<MOE_F32, 4> {
   typedef u32x4 type;
   __device__ static void widen(const u32x4& v, float* f) {
     f[0] = __uint_as_float(v.x);
@@ -155,13 +151,15 @@ struct Piece<float, 4> {
 };
 
 // A block produces kCombineRows output rows per iteration.
-template <typename TIn, typename TOut>
+template <int DIN, int DOUT>
 __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
     const void* __restrict__ y_sliced, const int32_t* __restrict__ inv_perm,
-    const float* __restrict__ gate_w, TOut* __restrict__ out, int T, int d, int top_k) {
-  constexpr int n = 16 / sizeof(TOut);
-  typedef Piece<TIn, n> P;
+    const float* __restrict__ gate_w, void* __restrict__ out_v, int T, int d, int top_k) {
+  constexpr int out_bytes = DOUT == MOE_F32 ? 4 : 2;
+  constexpr int n = 16 / out_bytes;
+  typedef Piece<DIN, n> P;
   const typename P::type* __restrict__ y = static_cast<const typename P::type*>(y_sliced);
+  unsigned char* out = static_cast<unsigned char*>(out_v);
   const int pieces_per_row = d / n;
   for (int t0 = blockIdx.x * kCombineRows; t0 < T; t0 += gridDim.x * kCombineRows) {
     for (int col = threadIdx.x; col < pieces_per_row; col += kCopyThreads) {
@@ -185,13 +183,13 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
 #pragma unroll
       for (int i = 0; i < kCombineRows; ++i) {
         if (t0 + i >= T) continue;
-        TOut* o = out + static_cast<int64_t>(t0 + i) * d + static_cast<int64_t>(col) * n;
-        if constexpr (sizeof(TOut) == 2) {
+        unsigned char* o = out + (static_cast<int64_t>(t0 + i) * pieces_per_row + col) * 16;
+        if constexpr (DOUT != MOE_F32) {
           u32x4 v;
-          v.x = pack_bf16x2(acc[i][0], acc[i][1]);
-          v.y = pack_bf16x2(acc[i][2], acc[i][3]);
-          v.z = pack_bf16x2(acc[i][4], acc[i][5]);
-          v.w = pack_bf16x2(acc[i][6], acc[i][7]);
+          v.x = Elem16<DOUT>::pack2(acc[i][0], acc[i][1]);
+          v.y = Elem16<DOUT>::pack2(acc[i][2], acc[i][3]);
+          v.z = Elem16<DOUT>::pack2(acc[i][4], acc[i][5]);
+          v.w = Elem16<DOUT>::pack2(acc[i][6], acc[i][7]);
           __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(o));
         } else {
           f32x4 v = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
@@ -207,16 +205,14 @@ hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32
   if (c.T == 0) return hipSuccess;
   int64_t want = (static_cast<int64_t>(c.T) + kCombineRows - 1) / kCombineRows;
   int blocks = static_cast<int>(want < 256 * kCombineBlocksPerCu ? want : 256 * kCombineBlocksPerCu);
-  const void* y = y_sliced;
-  if (c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16)
-    combine_kernel<bf16_t, bf16_t><<<blocks, kCopyThreads, 0, s>>>(
-        y, inv_perm, gate_w, static_cast<bf16_t*>(out), c.T, c.d, c.top_k);
-  else if (c.in_dtype == MOE_BF16)
-    combine_kernel<bf16_t, float><<<blocks, kCopyThreads, 0, s>>>(
-        y, inv_perm, gate_w, static_cast<float*>(out), c.T, c.d, c.top_k);
-  else
-    combine_kernel<float, float><<<blocks, kCopyThreads, 0, s>>>(
-        y, inv_perm, gate_w, static_cast<float*>(out), c.T, c.d, c.top_k);
+#define PPMOE_COMBINE(DIN, DOUT)                                  \
+  combine_kernel<DIN, DOUT><<<blocks, kCopyThreads, 0, s>>>(y_sliced, inv_perm, gate_w, out, c.T, c.d, c.top_k)
+  if (c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16) PPMOE_COMBINE(MOE_BF16, MOE_BF16);
+  else if (c.in_dtype == MOE_BF16) PPMOE_COMBINE(MOE_BF16, MOE_F32);
+  else if (c.in_dtype == MOE_F16 && c.out_dtype == MOE_F16) PPMOE_COMBINE(MOE_F16, MOE_F16);
+  else if (c.in_dtype == MOE_F16) PPMOE_COMBINE(MOE_F16, MOE_F32);
+  else PPMOE_COMBINE(MOE_F32, MOE_F32);
+#undef PPMOE_COMBINE
   return hipGetLastError();
 }
 

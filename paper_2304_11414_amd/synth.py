@@ -34,8 +34,8 @@ class LayerConfig:
     local_count: int = -1       # -1: all E
     capacity_factor: float = 0.0
     renorm_topk: bool = False
-    in_dtype: str = "bf16"      # "bf16" | "f32": tokens, router and expert weights, H, y_sliced
-    out_dtype: str = "bf16"     # "bf16" | "f32": the partial output
+    in_dtype: str = "bf16"      # "bf16" | "f16" | "f32": tokens, router and expert weights, H, y_sliced
+    out_dtype: str = "bf16"     # "bf16" | "f16" | "f32": the partial output
     seed: int = 0
     bias_kind: str = "none"     # "none" | "zipf": bias[e] = -bias_scale * bias_s * ln(e + 1)
     bias_s: float = 0.0
@@ -79,8 +79,16 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
     return a
 
 
+def round_to_f16(a: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest IEEE half (ties to even), returned as float32 (in place)."""
+    assert a.dtype == np.float32
+    a[...] = a.astype(np.float16).astype(np.float32)
+    return a
+
+
 def _normal(seed_seq, shape, std, bf16, threads=8):
-    """N(0, std) float32 array, drawn in independent row-chunks (one child seed per chunk)."""
+    """N(0, std) float32 array, drawn in independent row-chunks (one child seed per chunk).
+    bf16: False (keep float32), True or "bf16" (round to bf16), "f16" (round to IEEE half)."""
     out = np.empty(shape, dtype=np.float32)
     flat = out.reshape(-1)
     n = flat.size
@@ -94,7 +102,9 @@ def _normal(seed_seq, shape, std, bf16, threads=8):
         g.standard_normal(hi - lo, dtype=np.float32, out=flat[lo:hi])
         if std != 1.0:
             flat[lo:hi] *= np.float32(std)
-        if bf16:
+        if bf16 == "f16":
+            round_to_f16(flat[lo:hi])
+        elif bf16:
             round_to_bf16(flat[lo:hi])
 
     if n_chunks == 1:
@@ -117,7 +127,7 @@ def router_bias(cfg: LayerConfig):
 def make_inputs(cfg: LayerConfig, parts=("x", "Wg_t", "bias", "W1_t", "W2_t")):
     """Draw the layer's inputs.  Each tensor has its own child seed, so any subset can be drawn and
     is identical to the same tensor in a full draw."""
-    bf16 = cfg.in_dtype == "bf16"
+    bf16 = {"bf16": True, "f16": "f16", "f32": False}[cfg.in_dtype]
     root = np.random.SeedSequence([0x2304_1141, cfg.seed])
     s_x, s_wg, s_w1, s_w2 = root.spawn(4)
     N = cfg.n_local

@@ -64,6 +64,8 @@ def test_gate_given_logits_is_bit_exact(T, E, k, renorm):
     dict(T=700, d=1024, E=64, top_k=1, local_count=8),
     dict(T=130, d=264, E=100, top_k=3, renorm_topk=True),
     dict(T=70, d=128, E=200, top_k=2),
+    dict(T=1000, d=512, E=8, top_k=2, renorm_topk=True, in_dtype="f16", out_dtype="f16"),
+    dict(T=513, d=1024, E=64, top_k=1, in_dtype="f16", out_dtype="f32"),
 ])
 def test_gate_router(kw):
     lc = small_cfg(**kw)
@@ -208,6 +210,9 @@ def ragged_offsets(counts):
     ("bf16", 2048, 512, [32, 33, 64, 65, 128, 129, 0, 1]),   # every small-tile height boundary
     ("f32", 64, 136, [70, 0, 64, 1]),
     ("f32", 256, 1024, [64, 64, 64, 64]),
+    ("f16", 192, 520, [300, 0, 513, 1, 255, 256]),          # general 16-bit kernel (K not a multiple of 64)
+    ("f16", 512, 1024, [1024, 1000, 0, 24]),
+    ("f16", 4096, 256, [300, 3, 0, 257]),                   # tail tiles through the cut k-tile stream
 ])
 def test_expert_ffn_on_oracle_rows(dtype, d, F, counts):
     n = len(counts)
@@ -289,6 +294,8 @@ def test_handover_that_never_arrives_is_recomputed(d, F, counts):
     dict(T=1000, d=264, E=8, top_k=2, renorm_topk=True, capacity_factor=0.75),
     dict(T=999, d=128, E=16, top_k=2, local_begin=4, local_count=4, out_dtype="f32"),
     dict(T=300, d=64, E=4, top_k=3, in_dtype="f32", out_dtype="f32"),
+    dict(T=1000, d=264, E=8, top_k=2, renorm_topk=True, in_dtype="f16", out_dtype="f16"),
+    dict(T=999, d=128, E=16, top_k=2, local_begin=4, local_count=4, in_dtype="f16", out_dtype="f32"),
 ])
 def test_combine_on_oracle_rows(kw):
     lc = small_cfg(**kw)
@@ -300,13 +307,15 @@ def test_combine_on_oracle_rows(kw):
     y = np.random.default_rng(1).standard_normal((A, lc.d)).astype(np.float32)
     if lc.in_dtype == "bf16":
         synth.round_to_bf16(y)
+    elif lc.in_dtype == "f16":
+        synth.round_to_f16(y)
     w32 = w.astype(np.float32)
     ref = O.combine(y, inv, w32, lc.d)
     out = DeviceLayer(lc, {}).run_combine(y, inv, w32)
     none_kept = ~(inv >= 0).any(axis=1)
     assert none_kept.any() or lc.n_local == lc.E
     assert np.all(out[none_kept] == 0.0) and not np.signbit(out[none_kept]).any()
-    tol = 2.0 ** -8 if lc.out_dtype == "bf16" else 3e-7     # one rounding of the output type
+    tol = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 3e-7}[lc.out_dtype]   # one rounding of the output type
     assert_close(out, ref, tol, "out")
 
 
@@ -376,6 +385,11 @@ def test_layer_config1_fp32_full():
     dict(T=1500, d=256, F=1024, E=16, top_k=1, local_begin=4, local_count=8, seed=27),
     dict(T=2000, d=128, F=4096, E=8, top_k=1, capacity_factor=0.5, bias_kind="zipf", bias_s=1.1,
          seed=28),
+    # IEEE half, the paper's own precision (Section 4.1): fused top-1 path, top-2, float32 partial sum
+    dict(T=1200, d=256, F=512, E=8, top_k=1, in_dtype="f16", out_dtype="f16", seed=29),
+    dict(T=1200, d=256, F=2048, E=8, top_k=2, renorm_topk=True, in_dtype="f16", out_dtype="f16", seed=30),
+    dict(T=1500, d=256, F=1024, E=64, top_k=1, local_begin=8, local_count=8, in_dtype="f16", out_dtype="f32",
+         seed=33),
 ])
 def test_layer_medium_full(kw):
     lc = small_cfg(**kw)
@@ -543,10 +557,13 @@ def sampled_rows(info, T, n, seed, k):
     return np.array(sorted(rows))
 
 
-@pytest.mark.parametrize("ci,n_rows", [(1, 256), (2, 192), (3, 256), (4, 96), (5, 256)])
-def test_layer_full_size_configs_sampled(ci, n_rows):
+@pytest.mark.parametrize("ci,n_rows,dtype", [(1, 256, None), (2, 192, None), (3, 256, None), (4, 96, None),
+                                             (5, 256, None), (1, 128, "f16")])
+def test_layer_full_size_configs_sampled(ci, n_rows, dtype):
     from paper_2304_11414_amd import binding as B
     lc = synth.CONFIGS[ci]
+    if dtype is not None:   # the headline workload in the paper's own precision
+        lc = lc.scaled(name=f"{lc.name}_{dtype}", in_dtype=dtype, out_dtype=dtype)
     print(f"[{lc.name}] drawing inputs", flush=True)
     inp = synth.make_inputs(lc)
     mv = synth.math_views(inp)
@@ -581,12 +598,12 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
     np.testing.assert_array_equal(to_np(ws["inv_perm"]), info["inv_perm"])
     np.testing.assert_allclose(to_np(ws["gate_w"]), info["gate_w"], rtol=2e-4, atol=1e-7)
     got = to_np(out[dl.torch.from_numpy(rows).cuda()])
-    assert_close(got, ref_rows, TOL["bf16"], f"{lc.name} sampled out rows")
+    assert_close(got, ref_rows, TOL[lc.in_dtype], f"{lc.name} sampled out rows")
     # properties that hold at any size: zero rows are exact zeros, every other row is finite
     zero_rows = dl.torch.from_numpy(~(info["inv_perm"] >= 0).any(axis=1)).cuda()
     assert bool((out[zero_rows] == 0).all())
     assert bool(dl.torch.isfinite(out.float()).all())
-    assert max_rel_err(got, ref_rows) < TOL["bf16"]
+    assert max_rel_err(got, ref_rows) < TOL[lc.in_dtype]
     # The intermediates of the two expert GEMMs on the packed rows at the seams of their tiling
     # (first/last rows of every expert, both sides of every 256-row edge, the short tail tiles).
     print(f"[{lc.name}] H (and y_sliced) on the tile-edge rows", flush=True)
@@ -597,9 +614,9 @@ def test_layer_full_size_configs_sampled(ci, n_rows):
         x_sel = inp["x"][info["perm"][packed] // lc.top_k]
         H_ref, y_ref = O.expert_ffn(x_sel, np.array([0, packed.size]), mv["W1"][i:i + 1], mv["W2"][i:i + 1])
         sel = dl.torch.from_numpy(packed).cuda()
-        assert_close(to_np(ws["H"][sel]), H_ref, TOL["bf16"], f"{lc.name} H rows of expert {i}")
+        assert_close(to_np(ws["H"][sel]), H_ref, TOL[lc.in_dtype], f"{lc.name} H rows of expert {i}")
         if not fuses & B.MOE_FUSE_COMBINE:
-            assert_close(to_np(ws["y_sliced"][sel]), y_ref, TOL["bf16"], f"{lc.name} y rows of expert {i}")
+            assert_close(to_np(ws["y_sliced"][sel]), y_ref, TOL[lc.in_dtype], f"{lc.name} y rows of expert {i}")
 
 
 # ---------------------------------------------------------------------------- auxiliary loss
