@@ -268,14 +268,18 @@ int moe_layer_forward_aux(const moe_config* cfg, const void* x, const void* Wg, 
                           int32_t* first_counts, void* workspace, size_t workspace_bytes,
                           void* const* stage_events, void* stream);
 
-/* Which stages moe_layer_forward folds into the expert GEMMs for `cfg` (bf16 input, d a multiple
- * of 64): a mask of
+/* Which stages moe_layer_forward folds into the expert GEMMs for `cfg` (bf16 / fp16 input, d a
+ * multiple of 64): a mask of
  *   MOE_FUSE_SLICE    the first GEMM reads the token rows through the permutation (Algorithm 1's
  *                     index selection done by its loads): x_sliced is not written;
- *   MOE_FUSE_COMBINE  (top_k == 1, bf16 output, F a multiple of 64) the second GEMM applies the gate
- *                     weight and stores straight into `out` (the placement of the expert outputs
- *                     done by its stores): y_sliced is not written; rows of `out` without a kept
- *                     local pick are zeroed by a kernel of their own.
+ *   MOE_FUSE_COMBINE  (output of the input's 16-bit type, F a multiple of 64) the second GEMM applies the
+ *                     gate weight and stores straight into `out` every packed row that is its token's
+ *                     only kept local pick (the placement of the expert outputs done by its stores).
+ *                     top_k == 1: that is every row, y_sliced is not written, and rows of `out`
+ *                     without a kept local pick are zeroed by a kernel of their own.  top_k >= 2: rows
+ *                     of tokens with several kept local picks are still written to y_sliced and
+ *                     summed by the combine kernel, which leaves the placed rows alone; the other
+ *                     rows of y_sliced are not written.
  * 0: every intermediate is written. */
 enum { MOE_FUSE_SLICE = 1, MOE_FUSE_COMBINE = 2 };
 int moe_layer_fuses(const moe_config* cfg);

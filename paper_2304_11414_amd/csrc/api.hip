@@ -321,15 +321,16 @@ int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_
                                    static_cast<hipStream_t>(stream)));
 }
 
-// What moe_layer_forward folds into the expert GEMMs on the bf16 fast path.  Bit 0: the first GEMM
+// What moe_layer_forward folds into the expert GEMMs on the 16-bit fast path.  Bit 0: the first GEMM
 // reads the token rows through the permutation, so the sliced copy of the tokens is not made.
-// Bit 1 (top-1, bf16 output): the second GEMM multiplies by the gate weight and stores straight into
-// the layer output, so the packed expert outputs are not made either.
+// Bit 1 (output of the input type): the second GEMM multiplies by the gate weight and stores straight
+// into the layer output every row that is its token's only kept local pick (all of them under top-1:
+// the packed expert outputs are then not made at all; under top-k the others still go through
+// y_sliced and the combine kernel, which leaves the placed rows alone).
 static int layer_fuses(const moe_config& c) {
   if (!grouped_gemm_can_fuse(c.in_dtype, c.d, c.T)) return 0;
   int f = MOE_FUSE_SLICE;
-  if (c.top_k == 1 && c.out_dtype == c.in_dtype && grouped_gemm_is_fast(c.in_dtype, c.F))
-    f |= MOE_FUSE_COMBINE;
+  if (c.out_dtype == c.in_dtype && grouped_gemm_is_fast(c.in_dtype, c.F)) f |= MOE_FUSE_COMBINE;
   return f;
 }
 
@@ -425,13 +426,20 @@ int moe_layer_forward_aux(const moe_config* cfg, const void* x, const void* Wg, 
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, true, x_sliced, W1, H, offsets, c.local_count, rows,
                                   c.F, c.d, ws + L.gemm, s));
   PPMOE_TRY(mark(MOE_STAGE_FFN_DOWN));
-  if (fuses & MOE_FUSE_COMBINE) {
+  if ((fuses & MOE_FUSE_COMBINE) && c.top_k == 1) {
     // Tokens without a kept local pick exist only with a subset of the experts or a capacity limit.
     if (c.local_count < c.E || c.capacity_factor > 0.f)
       PPMOE_TRY(launch_zero_unrouted_rows(c, inv_perm, out, s));
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, out, offsets, c.local_count, rows, c.d,
                                   c.F, ws + L.gemm, s, 2, perm, gate_w));
     PPMOE_TRY(mark(MOE_STAGE_COMBINE));
+  } else if (fuses & MOE_FUSE_COMBINE) {
+    // top-k: rows that are their token's only kept local pick go straight into `out`; the combine
+    // kernel then writes the other tokens (sums of several picks, and zero rows) and skips those.
+    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, out, offsets, c.local_count, rows, c.d,
+                                  c.F, ws + L.gemm, s, 2, perm, gate_w, c.top_k, inv_perm, y_sliced));
+    PPMOE_TRY(mark(MOE_STAGE_COMBINE));
+    PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s, true));
   } else {
     PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, y_sliced, offsets, c.local_count, rows,
                                   c.d, c.F, ws + L.gemm, s));

@@ -135,8 +135,10 @@ hipError_t static_scratch_of_current_device(void** ptr);
 hipError_t launch_slice(const moe_config& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, void* x_sliced, int64_t max_rows, hipStream_t s);
 
+// skip_single: rows of tokens with exactly one kept local pick are left alone (the second GEMM has
+// already placed them, see launch_grouped_gemm fuse 2).
 hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
-                          const float* gate_w, void* out, hipStream_t s);
+                          const float* gate_w, void* out, hipStream_t s, bool skip_single = false);
 
 // Auxiliary balance loss from the logits and the picks; scratch: aux_scratch_bytes(c) bytes.
 size_t aux_scratch_bytes(const moe_config& c);
@@ -154,13 +156,15 @@ hipError_t launch_mfma_probe(int64_t iters, int random_operands, float* sink, in
 // C[r, :] = act(A[r, :] . B[i]^T) for offsets[i] <= r < offsets[i+1];  A [rows, K], B [n_exp, Nout, K].
 // workspace: grouped_gemm_workspace_bytes() of device scratch (partial sums of tiles cut between CUs).
 // fuse (only where grouped_gemm_can_fuse says so): 1: packed row r of A is row aux_rows[r] / aux_div
-// of the matrix given as A (first GEMM); 2: packed row r of the result, times aux_w[aux_rows[r]], is stored
-// as row aux_rows[r] of C (second GEMM; every such row of C is written at most once).
+// of the matrix given as A (first GEMM); 2 (second GEMM): packed row r of the result belongs to
+// assignment a = aux_rows[r] of token a / aux_div; if it is the only entry >= 0 of aux_inv[token, :]
+// it is stored, times aux_w[a], as row `token` of C (written by nobody else); else unweighted as
+// packed row r of C2 (aux_div == 1: always the former, aux_inv and C2 are not used).
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                void* workspace, hipStream_t s, int fuse = 0,
                                const int32_t* aux_rows = nullptr, const float* aux_w = nullptr,
-                               int aux_div = 1);
+                               int aux_div = 1, const int32_t* aux_inv = nullptr, void* C2 = nullptr);
 inline bool grouped_gemm_is_fast(int in_dtype, int K) {
   return is_16bit(in_dtype) && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
 }
@@ -190,7 +194,8 @@ void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit);
 hipError_t launch_grouped_gemm_fast(int in_dtype, bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
-                                    const int32_t* aux_rows, const float* aux_w, int aux_div);
+                                    const int32_t* aux_rows, const float* aux_w, int aux_div,
+                                    const int32_t* aux_inv, bf16_t* C2);
 
 // Most segments the permutation can be asked for: kSegment assignments each when it counts them
 // itself, the tokens of one wavefront of the gating kernel each when that kernel counts them.

@@ -308,12 +308,12 @@ static hipError_t ensure_lds_attr() {
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,
                                const int32_t* offsets, int n_exp, int64_t max_rows, int Nout, int K,
                                void* workspace, hipStream_t s, int fuse, const int32_t* aux_rows,
-                               const float* aux_w, int aux_div) {
+                               const float* aux_w, int aux_div, const int32_t* aux_inv, void* C2) {
   if (max_rows == 0) return hipSuccess;
   if (grouped_gemm_is_fast(in_dtype, K)) {
     return launch_grouped_gemm_fast(in_dtype, gelu, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
                                     static_cast<bf16_t*>(C), offsets, n_exp, max_rows, Nout, K, workspace, s,
-                                    fuse, aux_rows, aux_w, aux_div);
+                                    fuse, aux_rows, aux_w, aux_div, aux_inv, static_cast<bf16_t*>(C2));
   }
   if (fuse != 0) return hipErrorInvalidValue;   // the other kernels work on packed tensors only
   if (is_16bit(in_dtype)) {

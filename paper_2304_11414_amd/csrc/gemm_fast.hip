@@ -225,15 +225,19 @@ __global__ __launch_bounds__(kThreads) void xcc_probe_kernel() {
 
 // FUSE: 0: A and C are the packed tensors.  1: the rows of A are read through a list (packed row r is
 // row aux_rows[r] / aux_div of the matrix given as A): the index selection of Algorithm 1 done by
-// the loads of the first GEMM.  2: packed row r of the result is multiplied by aux_w[aux_rows[r]] and stored
-// as row aux_rows[r] of C: the placement of the expert outputs into the layer output done by the
-// stores of the second GEMM (top-1 only: a row of C is then written by at most one packed row).
+// the loads of the first GEMM.  2: the placement of the expert outputs into the layer output done by
+// the stores of the second GEMM: packed row r belongs to assignment a = aux_rows[r] of token
+// a / aux_div; if it is that token's only kept pick on this device (aux_inv[token, :] has no other
+// entry >= 0; always so with aux_div == 1) it is multiplied by aux_w[a] and stored as row `token` of
+// C, which nobody else writes; otherwise it is stored unweighted as packed row r of C2 and left to
+// the combine kernel, which has to add it to the token's other picks.
 template <bool GELU, int FUSE, int DT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int Nout, int K, float* __restrict__ slots,
     uint32_t* __restrict__ flags, uint32_t epoch, int same_l2, int spin_limit,
-    const int32_t* __restrict__ aux_rows, const float* __restrict__ aux_w, int aux_div) {
+    const int32_t* __restrict__ aux_rows, const float* __restrict__ aux_w, int aux_div,
+    const int32_t* __restrict__ aux_inv, bf16_t* __restrict__ C2) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int contrib[kMaxPersistentBlocks / 8 + 1];   // [0] = how many, then the block ids whose slots to add
   __shared__ int contrib_failed;
@@ -656,12 +660,25 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
     // The accumulators are read in exactly one place (one 32x32 block at a time), whichever way
     // they go: that keeps them in the accumulator registers until then.
     __builtin_amdgcn_s_barrier();   // every wavefront is done with the tile buffers
+    // FUSE == 2: where packed row r goes.  >= 0: row of C (the token; r is its only kept pick here);
+    // < 0: ~r, packed row r of C2.
+    auto placed_row = [&](int r, int& a_out) -> int {
+      const int a = aux_rows[r];
+      a_out = a;
+      if (aux_div == 1) return a;
+      const int t = a / aux_div;
+      int kept = 0;
+      for (int j = 0; j < aux_div; ++j) kept += aux_inv[t * aux_div + j] >= 0;
+      return kept == 1 ? t : ~r;
+    };
     float row_w[4] = {1.f, 1.f, 1.f, 1.f};   // FUSE == 2: gate weight of this lane's row of each row block
     if (FUSE == 2 && mode == 0) {
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
         const int row = min(row_base + mi * 32 + frow, tc.rows - 1);
-        row_w[mi] = aux_w[aux_rows[tc.row0 + row]];
+        int a;
+        const int dst = placed_row(tc.row0 + row, a);
+        row_w[mi] = dst >= 0 ? aux_w[a] : 1.f;
       }
     }
 #pragma unroll
@@ -772,13 +789,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       if (FUSE == 2) {
         int dst[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          dst[j] = aux_rows[tc.row0 + row_base + min((i0 + j) * 4 + er, max(nrow, 1) - 1)];
+        for (int j = 0; j < 8; ++j) {
+          int a;
+          dst[j] = placed_row(tc.row0 + row_base + min((i0 + j) * 4 + er, max(nrow, 1) - 1), a);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const int r = (i0 + j) * 4 + er;
-          if (r < nrow && ec * 8 < ncol)
-            *reinterpret_cast<u32x4*>(C + static_cast<size_t>(dst[j]) * Nout + tc.col0 + col_base + ec * 8) = v[j];
+          if (r < nrow && ec * 8 < ncol) {
+            bf16_t* base = dst[j] >= 0 ? C : C2;
+            const int row = dst[j] >= 0 ? dst[j] : ~dst[j];
+            *reinterpret_cast<u32x4*>(base + static_cast<size_t>(row) * Nout + tc.col0 + col_base + ec * 8) = v[j];
+          }
         }
       } else {
 #pragma unroll
@@ -912,7 +934,8 @@ void grouped_gemm_fast_set_handover(int force_device_scope, int spin_limit) {
 hipError_t launch_grouped_gemm_fast(int in_dtype, bool gelu, const bf16_t* A, const bf16_t* B, bf16_t* C,
                                     const int32_t* offsets, int n_exp, int64_t max_rows, int Nout,
                                     int K, void* workspace, hipStream_t s, int fuse,
-                                    const int32_t* aux_rows, const float* aux_w, int aux_div) {
+                                    const int32_t* aux_rows, const float* aux_w, int aux_div,
+                                    const int32_t* aux_inv, bf16_t* C2) {
   using namespace fast;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -947,15 +970,17 @@ hipError_t launch_grouped_gemm_fast(int in_dtype, bool gelu, const bf16_t* A, co
   uint32_t* flags = reinterpret_cast<uint32_t*>(
       slots + static_cast<size_t>(kSlotsPerBlock) * kMaxPersistentBlocks * kSlotFloats);
   (void)max_rows;
-  // fuse: 0 none; 1 rows of A through aux_rows (first GEMM only); 2 weighted rows of C placed through
-  // aux_rows (second GEMM only)
+  // fuse: 0 none; 1 rows of A through aux_rows (first GEMM only); 2 rows of the result placed through
+  // aux_rows (second GEMM only; with aux_div > 1 it needs the inverse permutation and a place for
+  // the rows it cannot place)
   if ((fuse == 1 && !gelu) || (fuse == 2 && gelu) || fuse < 0 || fuse > 2 ||
       (fuse != 0 && aux_rows == nullptr) || (fuse == 2 && aux_w == nullptr) || aux_div < 1 ||
-      (fuse == 2 && aux_div != 1))
+      (fuse == 2 && aux_div != 1 && (aux_inv == nullptr || C2 == nullptr)))
     return hipErrorInvalidValue;
 #define PPMOE_LAUNCH_DT(G, F, DT)                                                     \
   grouped_gemm_bf16_fast_kernel<G, F, DT><<<blocks, kThreads, kLdsBytes, s>>>(        \
-      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, spin_limit, aux_rows, aux_w, aux_div)
+      A, B, C, offsets, n_exp, Nout, K, slots, flags, epoch, same_l2, spin_limit, aux_rows, aux_w, aux_div, \
+      aux_inv, C2)
 #define PPMOE_LAUNCH(G, F)                            \
   do {                                                \
     if (in_dtype == MOE_F16) PPMOE_LAUNCH_DT(G, F, MOE_F16); \

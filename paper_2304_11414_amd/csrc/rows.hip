@@ -154,7 +154,7 @@ struct Piece<MOE_F32, 4> {
 template <int DIN, int DOUT>
 __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
     const void* __restrict__ y_sliced, const int32_t* __restrict__ inv_perm,
-    const float* __restrict__ gate_w, void* __restrict__ out_v, int T, int d, int top_k) {
+    const float* __restrict__ gate_w, void* __restrict__ out_v, int T, int d, int top_k, int skip_single) {
   constexpr int out_bytes = DOUT == MOE_F32 ? 4 : 2;
   constexpr int n = 16 / out_bytes;
   typedef Piece<DIN, n> P;
@@ -162,12 +162,25 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
   unsigned char* out = static_cast<unsigned char*>(out_v);
   const int pieces_per_row = d / n;
   for (int t0 = blockIdx.x * kCombineRows; t0 < T; t0 += gridDim.x * kCombineRows) {
+    // Rows already in place (skip_single: tokens with exactly one kept local pick, stored by the
+    // second expert GEMM) are neither read nor written.  (Uniform over the block.)
+    bool skip[kCombineRows];
+#pragma unroll
+    for (int i = 0; i < kCombineRows; ++i) {
+      skip[i] = false;
+      if (skip_single && t0 + i < T) {
+        int kept = 0;
+        for (int j = 0; j < top_k; ++j) kept += inv_perm[static_cast<int64_t>(t0 + i) * top_k + j] >= 0;
+        skip[i] = kept == 1;
+      }
+    }
     for (int col = threadIdx.x; col < pieces_per_row; col += kCopyThreads) {
       float acc[kCombineRows][n];
 #pragma unroll
       for (int i = 0; i < kCombineRows; ++i) {
 #pragma unroll
         for (int e = 0; e < n; ++e) acc[i][e] = 0.f;
+        if (skip[i]) continue;
         const int t = min(t0 + i, T - 1);
         for (int j = 0; j < top_k; ++j) {
           const int r = inv_perm[static_cast<int64_t>(t) * top_k + j];
@@ -183,6 +196,7 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
 #pragma unroll
       for (int i = 0; i < kCombineRows; ++i) {
         if (t0 + i >= T) continue;
+        if (skip[i]) continue;
         unsigned char* o = out + (static_cast<int64_t>(t0 + i) * pieces_per_row + col) * 16;
         if constexpr (DOUT != MOE_F32) {
           u32x4 v;
@@ -201,12 +215,13 @@ __global__ __launch_bounds__(kCopyThreads) void combine_kernel(
 }
 
 hipError_t launch_combine(const moe_config& c, const void* y_sliced, const int32_t* inv_perm,
-                          const float* gate_w, void* out, hipStream_t s) {
+                          const float* gate_w, void* out, hipStream_t s, bool skip_single) {
   if (c.T == 0) return hipSuccess;
   int64_t want = (static_cast<int64_t>(c.T) + kCombineRows - 1) / kCombineRows;
   int blocks = static_cast<int>(want < 256 * kCombineBlocksPerCu ? want : 256 * kCombineBlocksPerCu);
 #define PPMOE_COMBINE(DIN, DOUT)                                  \
-  combine_kernel<DIN, DOUT><<<blocks, kCopyThreads, 0, s>>>(y_sliced, inv_perm, gate_w, out, c.T, c.d, c.top_k)
+  combine_kernel<DIN, DOUT><<<blocks, kCopyThreads, 0, s>>>(y_sliced, inv_perm, gate_w, out, c.T, c.d, c.top_k, \
+                                                            skip_single ? 1 : 0)
   if (c.in_dtype == MOE_BF16 && c.out_dtype == MOE_BF16) PPMOE_COMBINE(MOE_BF16, MOE_BF16);
   else if (c.in_dtype == MOE_BF16) PPMOE_COMBINE(MOE_BF16, MOE_F32);
   else if (c.in_dtype == MOE_F16 && c.out_dtype == MOE_F16) PPMOE_COMBINE(MOE_F16, MOE_F16);
