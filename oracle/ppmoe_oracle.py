@@ -40,6 +40,10 @@ invariants in the tests):
   * the auxiliary balance loss ``l_aux`` that Algorithm 1 returns: the paper only says it follows
     GShard (Section 4.1) and prints no formula.  ``aux_loss`` below is the GShard form; it is pinned
     by closed forms and a scalar-loop restatement, not by anything the paper prints.
+
+The backward functions at the end (expert_ffn_backward, gate_backward, layer_backward) are the
+derivative of this forward by the chain rule (the paper prints no backward algorithm); they are
+pinned by central finite differences of the forward in the tests.
 """
 
 from __future__ import annotations
@@ -296,3 +300,119 @@ def ffn_flops(n_assignments, d, F):
     """Multiply-add count x2 of the two expert GEMMs for ``n_assignments`` kept rows; with F = 4d and
     one pick per token this is the 16*b*s*h^2 of Section 3.2."""
     return 4 * int(n_assignments) * int(d) * int(F)
+
+
+# ----------------------------------------------------------------------------------------------
+# Backward of the layer (Section 3.2, footnote to Eq. 1: the backward pass costs about twice the
+# forward; Section 3.3.4: it moves the same tensors between devices as the forward).  The paper
+# prints no backward algorithm: it trains through the automatic differentiation of its framework, so
+# what is written out here is the derivative of the forward above, term by term, by the chain rule.
+# The picks (top-k, capacity drops) are piecewise constant in the inputs and carry no gradient.
+# Everything is this device's partial sum, like the forward output: summed over the devices of a
+# tensor-parallel group it is the gradient of the whole layer.
+# ----------------------------------------------------------------------------------------------
+
+def gelu_tanh_grad(u):
+    """d/du of gelu_tanh.  With z = sqrt(2/pi) (u + 0.044715 u^3):
+    0.5 (1 + tanh z) + 0.5 u (1 - tanh^2 z) sqrt(2/pi) (1 + 3 * 0.044715 u^2)."""
+    u = np.asarray(u, dtype=F64)
+    c = math.sqrt(2.0 / math.pi)
+    th = np.tanh(c * (u + 0.044715 * u ** 3))
+    return 0.5 * (1.0 + th) + 0.5 * u * (1.0 - th * th) * c * (1.0 + 3.0 * 0.044715 * u * u)
+
+
+def expert_ffn_backward(x_sliced, offsets, W1, W2, dY):
+    """Backward of expert_ffn for each local expert i in turn, given dY = dLoss/dY (packed rows):
+
+        U_i = X_i A_i,  H_i = GeLU(U_i),  Y_i = H_i B_i
+        dH_i = dY_i B_i^T,  dU_i = dH_i * GeLU'(U_i),  dX_i = dU_i A_i^T,
+        dA_i = X_i^T dU_i,  dB_i = H_i^T dY_i.
+
+    W1[i] = A_i [d, F], W2[i] = B_i [F, d].  Returns dict(dX[A, d], dW1[N, d, F], dW2[N, F, d], U, H,
+    dH, dU), float64."""
+    x_sliced = np.asarray(x_sliced, dtype=F64)
+    dY = np.asarray(dY, dtype=F64)
+    n_local = len(offsets) - 1
+    A = int(offsets[-1])
+    d, F = W1[0].shape
+    U = np.zeros((A, F), dtype=F64)
+    H = np.zeros((A, F), dtype=F64)
+    dH = np.zeros((A, F), dtype=F64)
+    dU = np.zeros((A, F), dtype=F64)
+    dX = np.zeros((A, d), dtype=F64)
+    dW1 = np.zeros((n_local, d, F), dtype=F64)
+    dW2 = np.zeros((n_local, F, d), dtype=F64)
+    for i in range(n_local):
+        lo, hi = int(offsets[i]), int(offsets[i + 1])
+        if hi == lo:
+            continue
+        A_i = np.asarray(W1[i], dtype=F64)
+        B_i = np.asarray(W2[i], dtype=F64)
+        U[lo:hi] = x_sliced[lo:hi] @ A_i
+        H[lo:hi] = gelu_tanh(U[lo:hi])
+        dH[lo:hi] = dY[lo:hi] @ B_i.T
+        dU[lo:hi] = dH[lo:hi] * gelu_tanh_grad(U[lo:hi])
+        dX[lo:hi] = dU[lo:hi] @ A_i.T
+        dW1[i] = x_sliced[lo:hi].T @ dU[lo:hi]
+        dW2[i] = H[lo:hi].T @ dY[lo:hi]
+    return dict(dX=dX, dW1=dW1, dW2=dW2, U=U, H=H, dH=dH, dU=dU)
+
+
+def gate_backward(logits, expert_idx, renorm, d_gate_w):
+    """Gradient of the gate weights with respect to the logits, picks held fixed.
+
+    p = softmax(logits);  w_j = p[e_j], or p[e_j] / S with S = sum_j p[e_j] when renorm.
+    Without renorm  dp[e_j] = dw_j;  with renorm  dp[e_j] = (dw_j - sum_i dw_i w_i) / S.
+    Softmax:  dlogits[e] = p[e] (dp[e] - sum_e' dp[e'] p[e']).   Returns dlogits [T, E], float64."""
+    logits = np.asarray(logits, dtype=F64)
+    T, E = logits.shape
+    p = softmax_rows(logits)
+    idx = np.asarray(expert_idx).astype(np.int64)
+    dgw = np.asarray(d_gate_w, dtype=F64)
+    picked = np.take_along_axis(p, idx, axis=1)
+    if renorm:
+        S = picked.sum(axis=1, keepdims=True)
+        w = picked / S
+        dpick = (dgw - (dgw * w).sum(axis=1, keepdims=True)) / S
+    else:
+        dpick = dgw
+    dp = np.zeros((T, E), dtype=F64)
+    np.put_along_axis(dp, idx, dpick, axis=1)        # a token picks an expert at most once
+    return p * (dp - (dp * p).sum(axis=1, keepdims=True))
+
+
+def layer_backward(x, Wg, bias, W1, W2, d_out, *, E, k, local_begin, local_count,
+                   capacity_factor=0.0, renorm=False, logits_in=None, logits_dtype=np.float32):
+    """Backward of layer_forward given d_out = dLoss/d(out) [T, d]; the forward is re-evaluated first.
+
+        dY[r]       = gate_w[t, j] * d_out[t]                 for the kept local assignment (t, j) in row r
+        d_gate_w[t, j] = <d_out[t], Y[r]>                       (0 for dropped / non-local picks)
+        expert FFN backward                                     -> dX_sliced, dW1, dW2
+        dx[t]       = sum over kept local (t, j) of dX_sliced[r]  +  dlogits[t] Wg^T
+        dWg         = x^T dlogits,   dbias = column sums of dlogits
+
+    Returns a dict with every intermediate, float64."""
+    fwd = layer_forward(x, Wg, bias, W1, W2, E=E, k=k, local_begin=local_begin,
+                        local_count=local_count, capacity_factor=capacity_factor, renorm=renorm,
+                        logits_in=logits_in, logits_dtype=logits_dtype)
+    x64 = np.asarray(x, dtype=F64)
+    d_out = np.asarray(d_out, dtype=F64)
+    T, d = x64.shape
+    perm, inv_perm, gate_w = fwd["perm"], fwd["inv_perm"], fwd["gate_w"]
+    tok = perm.astype(np.int64) // k
+    pick = perm.astype(np.int64) % k
+    dY = gate_w[tok, pick][:, None] * d_out[tok]
+    d_gate_w = np.zeros((T, k), dtype=F64)
+    d_gate_w[tok, pick] = np.einsum("rc,rc->r", d_out[tok], fwd["y_sliced"])
+    ffn = expert_ffn_backward(fwd["x_sliced"], fwd["offsets"], W1, W2, dY)
+    dx = np.zeros((T, d), dtype=F64)
+    for j in range(k):
+        rows = inv_perm[:, j]
+        kept = np.flatnonzero(rows >= 0)
+        dx[kept] += ffn["dX"][rows[kept]]
+    dlogits = gate_backward(fwd["logits"], fwd["expert_idx"], renorm, d_gate_w)
+    Wg64 = np.asarray(Wg, dtype=F64)
+    dx_gate = dlogits @ Wg64.T
+    return dict(fwd=fwd, dY=dY, d_gate_w=d_gate_w, dX_sliced=ffn["dX"], dW1=ffn["dW1"], dW2=ffn["dW2"],
+                dU=ffn["dU"], dH=ffn["dH"], U=ffn["U"], dlogits=dlogits, dx_experts=dx, dx_gate=dx_gate,
+                dx=dx + dx_gate, dWg=x64.T @ dlogits, dbias=dlogits.sum(axis=0))

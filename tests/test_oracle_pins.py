@@ -443,3 +443,110 @@ def test_aux_loss_against_scalar_loops_and_invariances():
     # probabilities sum to one, shares sum to one; Cauchy-Schwarz-free bounds: 0 < l_aux <= E
     assert abs(r["mean_prob"].sum() - 1.0) < 1e-14 and r["first_counts"].sum() == T
     assert 0.0 < r["l_aux"] <= E
+
+
+# ------------------------------------------------------------------ backward (chain rule of the forward)
+
+def _fd_layer(theta, name, base, R, kw, eps=1e-6):
+    """Central finite difference of L = sum(out * R) with respect to every entry of one input."""
+    g = np.zeros_like(theta)
+    it = np.nditer(theta, flags=["multi_index"])
+    for _ in it:
+        idx = it.multi_index
+        vals = []
+        for sgn in (+1.0, -1.0):
+            args = {k: (v.copy() if isinstance(v, np.ndarray) else [m.copy() for m in v] if isinstance(v, list) else v)
+                    for k, v in base.items()}
+            if isinstance(args[name], list):
+                args[name][idx[0]][idx[1:]] += sgn * eps
+            else:
+                args[name][idx] += sgn * eps
+            out = O.layer_forward(args["x"], args["Wg"], args["bias"], args["W1"], args["W2"], logits_dtype=None,
+                                  **kw)["out"]
+            vals.append(np.sum(out * R))
+        g[idx] = (vals[0] - vals[1]) / (2 * eps)
+    return g
+
+
+@pytest.mark.parametrize("k,renorm,cf,local", [(1, False, 0.0, (0, 4)), (2, True, 0.0, (0, 4)), (2, False, 0.75, (0, 4)),
+                                               (2, True, 0.0, (1, 2)), (3, True, 1.0, (0, 4))])
+def test_layer_backward_against_finite_differences(k, renorm, cf, local):
+    """Every gradient layer_backward returns (tokens, router matrix and bias, both expert matrices)
+    against central differences of layer_forward, entry by entry, on a layer small enough for that;
+    gate weights and picks of top-1 / top-2 / top-3, renormalised or not, capacity drops, a subset of
+    the experts.  The picks stay fixed under the perturbation (the seed leaves margins)."""
+    rng = np.random.default_rng(100 + k)
+    T, d, F, E = 9, 5, 7, 4
+    base = dict(x=rng.standard_normal((T, d)), Wg=rng.standard_normal((d, E)), bias=0.3 * rng.standard_normal(E),
+                W1=[0.7 * rng.standard_normal((d, F)) for _ in range(E)],
+                W2=[0.7 * rng.standard_normal((F, d)) for _ in range(E)])
+    e0, n = local
+    kw = dict(E=E, k=k, local_begin=e0, local_count=n, capacity_factor=cf, renorm=renorm)
+    loc = dict(base, W1=base["W1"][e0:e0 + n], W2=base["W2"][e0:e0 + n])
+    R = rng.standard_normal((T, d))
+    logits = O.router_logits(base["x"], base["Wg"], base["bias"])
+    srt = -np.sort(-logits, axis=1)
+    assert (srt[:, :-1] - srt[:, 1:]).min() > 1e-3          # no pick flips under a 1e-6 perturbation
+    bw = O.layer_backward(loc["x"], loc["Wg"], loc["bias"], loc["W1"], loc["W2"], R, logits_dtype=None, **kw)
+    assert (bw["fwd"]["inv_perm"] >= 0).any()
+    tol = dict(rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(bw["dx"], _fd_layer(loc["x"], "x", loc, R, kw), **tol)
+    np.testing.assert_allclose(bw["dWg"], _fd_layer(loc["Wg"], "Wg", loc, R, kw), **tol)
+    np.testing.assert_allclose(bw["dbias"], _fd_layer(loc["bias"], "bias", loc, R, kw), **tol)
+    fd_w1 = _fd_layer(np.stack(loc["W1"]), "W1", loc, R, kw)
+    fd_w2 = _fd_layer(np.stack(loc["W2"]), "W2", loc, R, kw)
+    np.testing.assert_allclose(bw["dW1"], fd_w1, **tol)
+    np.testing.assert_allclose(bw["dW2"], fd_w2, **tol)
+    if cf > 0:
+        assert (bw["fwd"]["inv_perm"] < 0).any()              # the capacity did drop something
+
+
+def test_gelu_grad_against_finite_differences_and_limits():
+    u = np.linspace(-6, 6, 1201)
+    eps = 1e-6
+    fd = (O.gelu_tanh(u + eps) - O.gelu_tanh(u - eps)) / (2 * eps)
+    np.testing.assert_allclose(O.gelu_tanh_grad(u), fd, rtol=0, atol=1e-8)
+    assert O.gelu_tanh_grad(np.array([0.0]))[0] == 0.5
+    np.testing.assert_allclose(O.gelu_tanh_grad(np.array([9.0, -9.0])), [1.0, 0.0], atol=1e-12)
+    # The erf form has GeLU'' = phi(u) (2 - u^2), so its derivative is smallest at u = -sqrt(2), where it
+    # is Phi(-sqrt 2) - sqrt(2) phi(sqrt 2) = -0.12890; the tanh form stays within 1e-3 of that.  (With
+    # the factor 3 of the cubic term's derivative dropped the minimum is -0.0998 at u = -1.38.)
+    g = O.gelu_tanh_grad(u)
+    exact_min = 0.5 * (1 + math.erf(-1.0)) - math.sqrt(2) * math.exp(-1.0) / math.sqrt(2 * math.pi)
+    assert abs(exact_min - (-0.12890)) < 1e-5
+    assert abs(g.min() - exact_min) < 1e-3 and abs(u[np.argmin(g)] + math.sqrt(2)) < 0.03
+
+
+def test_expert_ffn_backward_reduces_to_the_dense_ffn_gradients():
+    """One expert holding every row: the textbook gradients of Y = GeLU(X A) B, written out with
+    numpy, and the finite difference of <Y, R> in a few entries of A and B."""
+    rng = np.random.default_rng(5)
+    n, d, F = 6, 4, 5
+    X, A, Bm, R = (rng.standard_normal(s) for s in ((n, d), (d, F), (F, d), (n, d)))
+    bw = O.expert_ffn_backward(X, np.array([0, n]), [A], [Bm], R)
+    U = X @ A
+    dU = (R @ Bm.T) * O.gelu_tanh_grad(U)
+    np.testing.assert_allclose(bw["dX"], dU @ A.T, rtol=1e-13)
+    np.testing.assert_allclose(bw["dW1"][0], X.T @ dU, rtol=1e-13)
+    np.testing.assert_allclose(bw["dW2"][0], O.gelu_tanh(U).T @ R, rtol=1e-13)
+    eps = 1e-6
+    for (i, j) in ((0, 0), (3, 4), (2, 1)):
+        Ap, Am = A.copy(), A.copy()
+        Ap[i, j] += eps
+        Am[i, j] -= eps
+        fd = (np.sum(O.gelu_tanh(X @ Ap) @ Bm * R) - np.sum(O.gelu_tanh(X @ Am) @ Bm * R)) / (2 * eps)
+        assert abs(bw["dW1"][0][i, j] - fd) < 1e-7
+
+
+def test_gate_backward_rows_sum_to_zero_and_renormalised_weights_have_no_common_mode():
+    """Softmax gradients sum to zero over the experts; with renormalised weights (which sum to one)
+    a d_gate_w that is constant over the picks gives no gradient at all."""
+    rng = np.random.default_rng(6)
+    logits = rng.standard_normal((11, 6))
+    idx = O.top_k_picks(logits, 3)
+    dgw = rng.standard_normal((11, 3))
+    for renorm in (False, True):
+        g = O.gate_backward(logits, idx, renorm, dgw)
+        np.testing.assert_allclose(g.sum(axis=1), 0.0, atol=1e-14)
+    g = O.gate_backward(logits, idx, True, np.full((11, 3), 2.5))
+    np.testing.assert_allclose(g, 0.0, atol=1e-14)
