@@ -217,6 +217,25 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
                    const void* W1, const void* W2, void* H, void* y_sliced, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/* Backward of the local experts (Section 3.2, footnote to Eq. 1: the backward pass costs about twice the
+ * forward; Section 3.3.4: it exchanges the same tensors; the paper prints no backward algorithm, this
+ * is the chain rule of moe_expert_ffn).  With U = x_sliced W1[i]^T, H = GeLU(U), y_sliced = H W2[i]^T
+ * for the packed rows offsets[i] <= r < offsets[i+1] of expert i, and dY = dLoss/dy_sliced:
+ *   dX_sliced[r, :] = (dY[r, :] W2[i] * GeLU'(U[r, :])) W1[i]            [rows, d]  in_dtype
+ *   dW1[i]          = sum_r (dY[r, :] W2[i] * GeLU'(U[r, :]))^T x_sliced[r, :]   [F, d]  float32
+ *   dW2[i]          = sum_r dY[r, :]^T H[r, :]                                     [d, F]  float32
+ * (the weight gradients in the weights' own [out, in] layout, overwritten, not accumulated; an expert
+ * without rows gets zeros).  U is recomputed from x_sliced, so the forward need keep nothing.
+ * in_dtype BF16 or F16 only (MOE_ERR_DTYPE otherwise).  x_sliced, dY, dX_sliced: [moe_max_rows, d];
+ * rows at or beyond offsets[local_count] are neither read nor written.
+ * workspace: at least moe_ffn_backward_workspace_bytes(cfg) bytes of device scratch (three
+ * [moe_max_rows, F] buffers and the expert GEMM's own scratch); the first expert-FFN call of a device
+ * may synchronise once, see moe_init. */
+size_t moe_ffn_backward_workspace_bytes(const moe_config* cfg);
+int moe_expert_ffn_backward(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                            const void* W1, const void* W2, const void* dY, void* dX_sliced, float* dW1,
+                            float* dW2, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Health of the expert-FFN calls that used `workspace` since the last check.  When an output tile
  * is cut between compute units, the partial sums are handed over through the workspace with a
  * bounded wait.  The persistent kernel expects one block per compute unit to be resident at once,

@@ -51,6 +51,8 @@ _PROTOTYPES = {
     "moe_expert_ffn_up": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
     "moe_expert_ffn_down": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5 + [c_size_t, c_void_p]),
     "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
+    "moe_ffn_backward_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
+    "moe_expert_ffn_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
@@ -212,6 +214,16 @@ def moe_expert_ffn(cfg, x_sliced, offsets, W1, W2, H, y_sliced, workspace, strea
     _check(load_library().moe_expert_ffn(byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1),
                                          _ptr(W2), _ptr(H), _ptr(y_sliced), _ptr(workspace),
                                          _nbytes(workspace), _stream(stream)), "moe_expert_ffn")
+
+
+def moe_ffn_backward_workspace_bytes(cfg) -> int:
+    return load_library().moe_ffn_backward_workspace_bytes(byref(cfg))
+
+
+def moe_expert_ffn_backward(cfg, x_sliced, offsets, W1, W2, dY, dX_sliced, dW1, dW2, workspace, stream=None):
+    _check(load_library().moe_expert_ffn_backward(
+        byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1), _ptr(W2), _ptr(dY), _ptr(dX_sliced), _ptr(dW1),
+        _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)), "moe_expert_ffn_backward")
 
 
 def moe_ffn_check(cfg, workspace, layer_workspace, stream=None) -> int:

@@ -290,6 +290,29 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
   return moe_expert_ffn_down(cfg, H, offsets, W2, y_sliced, workspace, workspace_bytes, stream);
 }
 
+size_t moe_ffn_backward_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK || !is_16bit(cfg->in_dtype)) return 0;
+  return expert_ffn_backward_scratch_bytes(*cfg, max_rows_of(*cfg));
+}
+
+int moe_expert_ffn_backward(const moe_config* cfg, const void* x_sliced, const int32_t* offsets,
+                            const void* W1, const void* W2, const void* dY, void* dX_sliced, float* dW1,
+                            float* dW2, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (!is_16bit(cfg->in_dtype)) return MOE_ERR_DTYPE;
+  if (x_sliced == nullptr || offsets == nullptr || W1 == nullptr || W2 == nullptr || dY == nullptr ||
+      dX_sliced == nullptr || dW1 == nullptr || dW2 == nullptr || workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(x_sliced) || misaligned(offsets) || misaligned(W1) || misaligned(W2) || misaligned(dY) ||
+      misaligned(dX_sliced) || misaligned(dW1) || misaligned(dW2) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  const int64_t rows = max_rows_of(*cfg);
+  if (workspace_bytes < expert_ffn_backward_scratch_bytes(*cfg, rows)) return MOE_ERR_WORKSPACE;
+  return hip_status(launch_expert_ffn_backward(*cfg, rows, x_sliced, offsets, W1, W2, dY, dX_sliced, dW1, dW2,
+                                               workspace, static_cast<hipStream_t>(stream)));
+}
+
 int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
                   int32_t* status, void* stream) {
   int st = check_config(cfg);

@@ -165,6 +165,14 @@ hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const voi
                                void* workspace, hipStream_t s, int fuse = 0,
                                const int32_t* aux_rows = nullptr, const float* aux_w = nullptr,
                                int aux_div = 1, const int32_t* aux_inv = nullptr, void* C2 = nullptr);
+// Backward of the expert FFN on the packed rows (16-bit types only): dX [rows, d] 16-bit,
+// dW1 [n_exp, F, d] and dW2 [n_exp, d, F] float32; scratch: expert_ffn_backward_scratch_bytes bytes.
+size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows);
+hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
+                                      const int32_t* offsets, const void* W1, const void* W2,
+                                      const void* dY, void* dX, float* dW1, float* dW2, void* scratch,
+                                      hipStream_t s);
+
 inline bool grouped_gemm_is_fast(int in_dtype, int K) {
   return is_16bit(in_dtype) && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel
 }

@@ -133,6 +133,31 @@ class DeviceLayer:
         assert status == 0, "a hand-over of partial sums did not arrive"
         return to_np(H[:n]), to_np(y[:n])
 
+    def run_ffn_backward(self, x_sliced, offsets, dY):
+        """moe_expert_ffn_backward on packed rows; returns (dX[:n], dW1 [N,F,d], dW2 [N,d,F]) as NumPy."""
+        t, c = self.torch, self.cfg
+        et = torch_dtype(self.lc.in_dtype)
+        rows = max(self.rows, 1)
+        xs = self.empty((rows, c.d), et)
+        dy = self.empty((rows, c.d), et)
+        xs.fill_(float("nan"))                     # rows past the last packed row must not be read
+        dy.fill_(float("nan"))
+        n = x_sliced.shape[0]
+        if n:
+            xs[:n] = to_dev(np.asarray(x_sliced, dtype=np.float32), self.lc.in_dtype)
+            dy[:n] = to_dev(np.asarray(dY, dtype=np.float32), self.lc.in_dtype)
+        off = to_dev(np.asarray(offsets, dtype=np.int32))
+        dX = self.empty((rows, c.d), et)
+        dX.fill_(5.0)
+        dW1 = t.full((c.local_count, c.F, c.d), 7.0, dtype=t.float32, device="cuda")
+        dW2 = t.full((c.local_count, c.d, c.F), 7.0, dtype=t.float32, device="cuda")
+        ws = self.empty((B.moe_ffn_backward_workspace_bytes(c),), t.uint8)
+        ws.fill_(0xFF)
+        B.moe_expert_ffn_backward(c, xs, off, self.W1, self.W2, dy, dX, dW1, dW2, ws)
+        t.cuda.synchronize()
+        assert bool((dX[n:] == 5.0).all()), "rows past the last packed row were written"
+        return to_np(dX[:n]), to_np(dW1), to_np(dW2)
+
     def run_combine(self, y_sliced, inv_perm, gate_w):
         t, c = self.torch, self.cfg
         y = self.empty((max(self.rows, 1), c.d), torch_dtype(self.lc.in_dtype))

@@ -287,6 +287,40 @@ def test_handover_that_never_arrives_is_recomputed(d, F, counts):
     assert status == 0
 
 
+@pytest.mark.parametrize("dtype,d,F,counts", [
+    ("bf16", 64, 128, [5, 0, 300]),
+    ("bf16", 192, 520, [300, 0, 513, 1, 255, 256]),
+    ("bf16", 200, 264, [257, 31]),
+    ("bf16", 512, 1024, [1024, 1000, 0, 24]),
+    ("bf16", 1024, 256, [129, 128, 600, 3]),
+    ("f16", 256, 512, [300, 0, 130, 1]),
+])
+def test_expert_ffn_backward_on_oracle_rows(dtype, d, F, counts):
+    """moe_expert_ffn_backward against the oracle's chain rule on ragged groups (empty experts, one-row
+    experts, rows and sizes that are not multiples of the tile): data gradient in the layer's 16-bit
+    type, both weight gradients in float32."""
+    n = len(counts)
+    A = int(sum(counts))
+    lc = small_cfg(T=A, d=d, F=F, E=n, top_k=1, in_dtype=dtype, out_dtype=dtype, seed=d + F + 1)
+    inp = synth.make_inputs(lc, parts=("x", "W1_t", "W2_t"))
+    inp["W1_t"] *= 8.0                                   # the GeLU and its derivative see their whole range
+    inp["W2_t"] *= 8.0
+    mv = synth.math_views(inp)
+    offsets = ragged_offsets(counts)
+    dY = np.random.default_rng(d * F).standard_normal((A, d)).astype(np.float32)
+    (synth.round_to_bf16 if dtype == "bf16" else synth.round_to_f16)(dY)
+    ref = O.expert_ffn_backward(inp["x"], offsets, mv["W1"], mv["W2"], dY)
+    dl = DeviceLayer(lc, inp)
+    dX, dW1, dW2 = dl.run_ffn_backward(inp["x"], offsets, dY)
+    tol = TOL[dtype]
+    assert_close(dX, ref["dX"], tol, "dX_sliced")
+    assert_close(dW1, ref["dW1"].transpose(0, 2, 1), tol, "dW1")       # library layout [N, F, d]
+    assert_close(dW2, ref["dW2"].transpose(0, 2, 1), tol, "dW2")       # library layout [N, d, F]
+    for i, cnt in enumerate(counts):
+        if cnt == 0:
+            assert not dW1[i].any() and not dW2[i].any()
+
+
 # ------------------------------------------------------------------------------------------ combine
 
 @pytest.mark.parametrize("kw", [
