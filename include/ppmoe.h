@@ -236,6 +236,26 @@ int moe_expert_ffn_backward(const moe_config* cfg, const void* x_sliced, const i
                             const void* W1, const void* W2, const void* dY, void* dX_sliced, float* dW1,
                             float* dW2, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Backward of the whole layer (the chain rule of moe_layer_forward with the picks -- top-k and capacity
+ * drops -- held fixed; Section 3.2, footnote to Eq. 1; Section 3.3.4: in a tensor-parallel group the
+ * backward exchanges the same tensors as the forward, i.e. one all-reduce of dx, outside this call).
+ * Given d_out = dLoss/d(out) [T, d] in out_dtype, with (t, j) -> r the kept local assignments:
+ *   dY[r, :]       = gate_w[t, j] * d_out[t, :]
+ *   d_gate_w[t, j] = <d_out[t, :], y_sliced[r, :]>   (0 for dropped or non-local picks)
+ *   dlogits        = d_gate_w through the (renormalised) top-k weights and the softmax
+ *   dx[t, :]       = sum over kept local (t, j) of dX_sliced[r, :]  +  dlogits[t, :] Wg     [T, d]  in_dtype
+ *   dWg            = dlogits^T x   [E, d] float32;   dbias = column sums of dlogits   [E] float32 or NULL
+ *   dW1, dW2       as in moe_expert_ffn_backward
+ * Everything is this device's partial sum: over the devices of a tensor-parallel group dx, dWg and
+ * dbias add up to the gradients of the whole layer (a pick that is local elsewhere contributes there).
+ * The gradient of l_aux is not included.  The routing is recomputed from x and Wg, so nothing has to be
+ * kept from the forward call.  in_dtype BF16 or F16 only.
+ * workspace: at least moe_layer_backward_workspace_bytes(cfg) bytes of device scratch. */
+size_t moe_layer_backward_workspace_bytes(const moe_config* cfg);
+int moe_layer_backward(const moe_config* cfg, const void* x, const void* Wg, const float* bias, const void* W1,
+                       const void* W2, const void* d_out, void* dx, float* dWg, float* dbias, float* dW1,
+                       float* dW2, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Health of the expert-FFN calls that used `workspace` since the last check.  When an output tile
  * is cut between compute units, the partial sums are handed over through the workspace with a
  * bounded wait.  The persistent kernel expects one block per compute unit to be resident at once,

@@ -53,6 +53,8 @@ _PROTOTYPES = {
     "moe_expert_ffn": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "moe_ffn_backward_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_expert_ffn_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
+    "moe_layer_backward_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
+    "moe_layer_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
@@ -224,6 +226,17 @@ def moe_expert_ffn_backward(cfg, x_sliced, offsets, W1, W2, dY, dX_sliced, dW1, 
     _check(load_library().moe_expert_ffn_backward(
         byref(cfg), _ptr(x_sliced), _ptr(offsets), _ptr(W1), _ptr(W2), _ptr(dY), _ptr(dX_sliced), _ptr(dW1),
         _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)), "moe_expert_ffn_backward")
+
+
+def moe_layer_backward_workspace_bytes(cfg) -> int:
+    return load_library().moe_layer_backward_workspace_bytes(byref(cfg))
+
+
+def moe_layer_backward(cfg, x, Wg, bias, W1, W2, d_out, dx, dWg, dbias, dW1, dW2, workspace, stream=None):
+    _check(load_library().moe_layer_backward(
+        byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(d_out), _ptr(dx), _ptr(dWg),
+        _ptr(dbias), _ptr(dW1), _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+        "moe_layer_backward")
 
 
 def moe_ffn_check(cfg, workspace, layer_workspace, stream=None) -> int:

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libppmoe.so")
-SOURCES = ["api.hip", "gate.hip", "permute.hip", "rows.hip", "gemm.hip", "gemm_fast.hip", "gemm_bwd.hip", "probe.hip", "aux.hip"]
+SOURCES = ["api.hip", "gate.hip", "permute.hip", "rows.hip", "gemm.hip", "gemm_fast.hip", "gemm_bwd.hip", "layer_bwd.hip", "probe.hip", "aux.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed-FP32 instructions.
 HIPCC_FLAGS = [

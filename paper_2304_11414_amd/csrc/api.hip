@@ -313,6 +313,109 @@ int moe_expert_ffn_backward(const moe_config* cfg, const void* x_sliced, const i
                                                workspace, static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+
+// Where moe_layer_backward keeps its intermediates.
+struct backward_layout {
+  size_t scratch, expert_idx, gate_w, counts, offsets, perm, inv_perm, logits, dlogits, row_dot, x_sliced, dY,
+      dX_sliced, dwg, ffn;
+};
+
+void backward_layout_of(const moe_config& c, backward_layout* L, size_t* total) {
+  const size_t tk = static_cast<size_t>(c.T) * c.top_k;
+  const size_t rows = static_cast<size_t>(max_rows_of(c));
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes);
+    return at;
+  };
+  L->scratch = take(dispatch_scratch_bytes(c));
+  L->expert_idx = take(tk * 4);
+  L->gate_w = take(tk * 4);
+  L->counts = take(static_cast<size_t>(c.local_count) * 4);
+  L->offsets = take(static_cast<size_t>(c.local_count + 1) * 4);
+  L->perm = take(rows * 4);
+  L->inv_perm = take(tk * 4);
+  L->logits = take(static_cast<size_t>(c.T) * c.E * 4);
+  L->dlogits = take(static_cast<size_t>(c.T) * c.E * 4);
+  L->row_dot = take(rows * 4);
+  L->x_sliced = take(rows * c.d * 2);
+  L->dY = take(rows * c.d * 2);
+  L->dX_sliced = take(rows * c.d * 2);
+  L->dwg = take(dwg_scratch_bytes(c));
+  L->ffn = take(expert_ffn_backward_scratch_bytes(c, max_rows_of(c)));
+  *total = off;
+}
+
+}  // namespace
+
+size_t moe_layer_backward_workspace_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK || !is_16bit(cfg->in_dtype)) return 0;
+  backward_layout L;
+  size_t total = 0;
+  backward_layout_of(*cfg, &L, &total);
+  return total;
+}
+
+int moe_layer_backward(const moe_config* cfg, const void* x, const void* Wg, const float* bias, const void* W1,
+                       const void* W2, const void* d_out, void* dx, float* dWg, float* dbias, float* dW1,
+                       float* dW2, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (!is_16bit(cfg->in_dtype)) return MOE_ERR_DTYPE;
+  if (x == nullptr || Wg == nullptr || W1 == nullptr || W2 == nullptr || d_out == nullptr || dx == nullptr ||
+      dWg == nullptr || dW1 == nullptr || dW2 == nullptr || workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(Wg) || misaligned(bias) || misaligned(W1) || misaligned(W2) ||
+      misaligned(d_out) || misaligned(dx) || misaligned(dWg) || misaligned(dbias) || misaligned(dW1) ||
+      misaligned(dW2) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  backward_layout L;
+  size_t total = 0;
+  backward_layout_of(*cfg, &L, &total);
+  if (workspace_bytes < total) return MOE_ERR_WORKSPACE;
+
+  const moe_config& c = *cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int32_t* expert_idx = reinterpret_cast<int32_t*>(ws + L.expert_idx);
+  float* gate_w = reinterpret_cast<float*>(ws + L.gate_w);
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+  int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(ws + L.inv_perm);
+  int32_t* seg_scratch = reinterpret_cast<int32_t*>(ws + L.scratch);
+  float* logits = reinterpret_cast<float*>(ws + L.logits);
+  float* dlogits = reinterpret_cast<float*>(ws + L.dlogits);
+  float* row_dot = reinterpret_cast<float*>(ws + L.row_dot);
+  const int64_t rows = max_rows_of(c);
+#define PPMOE_TRY(expr)                            \
+  do {                                             \
+    if ((expr) != hipSuccess) return MOE_ERR_HIP;  \
+  } while (0)
+  // The forward's routing is recomputed (the gating kernel reads x once; nothing has to be kept from
+  // the forward call), this time with the logits written out for the softmax's derivative.
+  GateFusion fusion = {};
+  const bool fused_gate = gate_is_fused_kernel(c);
+  if (fused_gate) fusion.seg_count = seg_scratch;
+  PPMOE_TRY(launch_gate(c, x, Wg, bias, nullptr, logits, expert_idx, gate_w, s, fused_gate ? &fusion : nullptr));
+  if (fusion.seg_assign > 0)
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s,
+                             fusion.seg_assign, true, nullptr));
+  else
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s));
+  PPMOE_TRY(launch_slice(c, x, perm, offsets, ws + L.x_sliced, rows, s));
+  PPMOE_TRY(launch_gather_scale(c, d_out, perm, offsets, gate_w, ws + L.dY, rows, s));
+  PPMOE_TRY(launch_expert_ffn_backward(c, rows, ws + L.x_sliced, offsets, W1, W2, ws + L.dY, ws + L.dX_sliced, dW1,
+                                       dW2, ws + L.ffn, s, row_dot));
+  PPMOE_TRY(launch_gate_backward(c, logits, expert_idx, gate_w, inv_perm, row_dot, dlogits, s));
+  PPMOE_TRY(launch_dx(c, ws + L.dX_sliced, inv_perm, dlogits, Wg, dx, s));
+  PPMOE_TRY(launch_dwg(c, x, dlogits, dWg, dbias, ws + L.dwg, s));
+#undef PPMOE_TRY
+  return MOE_OK;
+}
+
 int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
                   int32_t* status, void* stream) {
   int st = check_config(cfg);

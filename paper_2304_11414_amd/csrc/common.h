@@ -171,7 +171,26 @@ size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows);
 hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
                                       const int32_t* offsets, const void* W1, const void* W2,
                                       const void* dY, void* dX, float* dW1, float* dW2, void* scratch,
-                                      hipStream_t s);
+                                      hipStream_t s, float* row_dot = nullptr);
+// row_dot (may be nullptr): [rows] float32, row_dot[r] = <dY[r, :], y_sliced[r, :]> (the derivative
+// with respect to a scale factor of row r of the expert output).
+
+// The pieces of the layer's backward that are not the expert FFN (layer_bwd.hip).
+// dY[r, :] = gate_w[perm[r]] * d_out[perm[r] / k, :]  (d_out in out_dtype, dY in in_dtype)
+hipError_t launch_gather_scale(const moe_config& c, const void* d_out, const int32_t* perm,
+                               const int32_t* offsets, const float* gate_w, void* dY, int64_t max_rows,
+                               hipStream_t s);
+// dlogits[t, :] from the logits, the picks, the gate weights and row_dot (see gate backward in the header)
+hipError_t launch_gate_backward(const moe_config& c, const float* logits, const int32_t* expert_idx,
+                                const float* gate_w, const int32_t* inv_perm, const float* row_dot,
+                                float* dlogits, hipStream_t s);
+// dx[t, :] = sum over kept local picks of dX_sliced[inv_perm[t, j], :] + dlogits[t, :] Wg   (in_dtype)
+hipError_t launch_dx(const moe_config& c, const void* dX_sliced, const int32_t* inv_perm,
+                     const float* dlogits, const void* Wg, void* dx, hipStream_t s);
+// dWg[e, :] = sum_t dlogits[t, e] x[t, :],  dbias[e] = sum_t dlogits[t, e]; scratch: dwg_scratch_bytes(c)
+size_t dwg_scratch_bytes(const moe_config& c);
+hipError_t launch_dwg(const moe_config& c, const void* x, const float* dlogits, float* dWg, float* dbias,
+                      void* scratch, hipStream_t s);
 
 inline bool grouped_gemm_is_fast(int in_dtype, int K) {
   return is_16bit(in_dtype) && (K % 64) == 0 && K < (1 << 22);   // 32-bit panel offsets in the fast kernel

@@ -10,13 +10,13 @@
 // and the two weight gradients contract over the packed rows of the expert
 //   dW2[i][c, f] = sum_r dY[r, c] H[r, f],        dW1[i][f, c] = sum_r dU[r, f] X[r, c],
 // so in both an operand reaches the matrix cores across its rows.  One kernel covers the two forms:
-// 128 x 128 x 32 block tile, four wavefronts (2 x 2), each 64 x 64 as 2 x 2 MFMA 32x32x16; operand
-// tiles go through LDS as [row][k] with k contiguous (rows 80 bytes apart: the 16 rows a
-// ds_read_b128 serves per cycle fall into different banks); an operand whose k runs along memory
-// rows is transposed on its way into LDS (16-byte global loads of 8 consecutive rows-of-the-tile at
-// one k, eight 2-byte LDS stores).  Weight gradients are float32 (the precision gradients are
-// accumulated in); data gradients have the layer's 16-bit type.  Sums have a fixed order: bitwise
-// reproducible.
+// 128 x 128 x 64 block tile, four wavefronts (2 x 2), each 64 x 64 as 2 x 2 MFMA 32x32x16; operand
+// tiles go through LDS as [row][k] with k contiguous (rows 144 bytes apart, 16-byte chunks
+// XOR-swizzled: fragment reads and staging writes are free of bank conflicts); an operand whose k
+// runs along memory rows is transposed in registers on its way into LDS (a thread loads an 8 x 8
+// block as eight 16-byte pieces, one per memory row, and writes eight 16-byte chunks, one per tile
+// row).  Weight gradients are float32 (the precision gradients are accumulated in); data gradients
+// have the layer's 16-bit type.  Sums have a fixed order: bitwise reproducible.
 
 #include "common.h"
 
@@ -24,57 +24,81 @@ namespace ppmoe {
 
 namespace bwd {
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int kThreads = 256;
-constexpr int kRowBytes = 80;                 // one tile row in LDS: 32 k-values (64 bytes) + 16 bytes of skew
-constexpr int kTileBytes = BM * kRowBytes;    // 10 KiB per operand tile
+constexpr int kRowBytes = 144;                // one tile row in LDS: 64 k-values (128 bytes) + 16 bytes of skew
+constexpr int kTileBytes = BM * kRowBytes;    // 18 KiB per operand tile
 constexpr int kStages = 2;
+constexpr int kLdsBytes = kStages * 2 * kTileBytes;   // 72 KiB
+
+// Byte offset of 16-byte chunk `ch` (8 k-values) of tile row `row`: chunks are XOR-swizzled with the
+// row's group of 16, so that the eight rows a thread writes after its in-register transpose, 16 rows
+// apart from the next lane's, and the 16 consecutive rows a fragment read serves per cycle both
+// spread over all banks.
+__device__ __forceinline__ int lds_chunk(int row, int ch) {
+  return row * kRowBytes + ((ch ^ ((row >> 4) & 7)) << 4);
+}
 
 // What one operand tile looks like in memory.  `base` points at element (tile row 0, k = 0).
-// row_major_k: k is contiguous (element (row, k) at base + row * ld + k); else the tile row index is
-// contiguous (element (row, k) at base + k * ld + row).  rows / ks: how many tile rows / k values
-// are valid from base on (the rest reads as zero).
+// K-contiguous: element (row, k) at base + row * ld + k; else the tile row index is contiguous:
+// element (row, k) at base + k * ld + row.  rows / ks: how many tile rows / k values are valid from
+// base on (the rest reads as zero).
 struct Operand {
   const bf16_t* base;
   int64_t ld;
   int rows, ks;
 };
 
-// Stage one 128 x 32 operand tile (k-tile starting at k0) into registers: 2 pieces of 16 bytes per thread.
+// One operand tile is 128 rows x 64 k = 1024 chunks of 16 bytes, staged by two wavefronts (half: which
+// of the two), eight chunks per thread.
+//  * k contiguous in memory: lane = (row % 8) * 8 + chunk; eight lanes read one whole 128-byte line.
+//  * rows contiguous in memory: a thread reads an 8 (k) x 8 (rows) block, one 16-byte piece from each
+//    of eight consecutive memory rows (16 lanes read 256 contiguous bytes of each), transposes it in
+//    registers (v_perm_b32) and writes eight 16-byte chunks, one per tile row.
 template <bool K_CONTIGUOUS>
-__device__ __forceinline__ void load_tile(const Operand& op, int k0, u32x4 (&v)[2]) {
+__device__ __forceinline__ void load_tile(const Operand& op, int k0, int half, int lane, u32x4 (&v)[8]) {
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  if (K_CONTIGUOUS) {
+    const int ch = lane & 7;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int p = threadIdx.x + i * kThreads;
-    if (K_CONTIGUOUS) {
-      const int row = p >> 2, kc = (p & 3) * 8;   // 4 pieces per row
-      const bool ok = row < op.rows && k0 + kc < op.ks;
-      v[i] = ok ? *reinterpret_cast<const u32x4*>(op.base + row * op.ld + k0 + kc) : zero;
-    } else {
-      const int k = p >> 4, rc = (p & 15) * 8;    // 16 pieces per memory row (one k)
-      const bool ok = k0 + k < op.ks && rc < op.rows;
-      v[i] = ok ? *reinterpret_cast<const u32x4*>(op.base + (k0 + k) * op.ld + rc) : zero;
+    for (int i = 0; i < 8; ++i) {
+      const int row = (lane >> 3) + 8 * half + 16 * i;
+      const bool ok = row < op.rows && k0 + ch * 8 < op.ks;
+      v[i] = ok ? *reinterpret_cast<const u32x4*>(op.base + row * op.ld + k0 + ch * 8) : zero;
+    }
+  } else {
+    const int rg = lane & 15, kg = half * 4 + (lane >> 4);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const int k = k0 + kg * 8 + kk;
+      const bool ok = k < op.ks && rg * 8 < op.rows;
+      v[kk] = ok ? *reinterpret_cast<const u32x4*>(op.base + k * op.ld + rg * 8) : zero;
     }
   }
 }
 
 template <bool K_CONTIGUOUS>
-__device__ __forceinline__ void store_tile(unsigned char* lds_tile, const u32x4 (&v)[2]) {
+__device__ __forceinline__ void store_tile(unsigned char* lds_tile, int half, int lane, const u32x4 (&v)[8]) {
+  if (K_CONTIGUOUS) {
+    const int ch = lane & 7;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int p = threadIdx.x + i * kThreads;
-    if (K_CONTIGUOUS) {
-      const int row = p >> 2, kc = p & 3;
-      *reinterpret_cast<u32x4*>(lds_tile + row * kRowBytes + kc * 16) = v[i];
-    } else {
-      const int k = p >> 4, rc = (p & 15) * 8;
-      const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    for (int i = 0; i < 8; ++i) {
+      const int row = (lane >> 3) + 8 * half + 16 * i;
+      *reinterpret_cast<u32x4*>(lds_tile + lds_chunk(row, ch)) = v[i];
+    }
+  } else {
+    const int rg = lane & 15, kg = half * 4 + (lane >> 4);
+    // v[kk] dword q holds tile rows 2q (low half) and 2q + 1 (high half) at k = kk; the chunk of tile
+    // row r wants, in dword q, k = 2q (low) and 2q + 1 (high).
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint16_t e = static_cast<uint16_t>(w[j >> 1] >> ((j & 1) * 16));
-        *reinterpret_cast<uint16_t*>(lds_tile + (rc + j) * kRowBytes + k * 2) = e;
-      }
+    for (int r = 0; r < 8; ++r) {
+      u32x4 o;
+      const uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
+      o.x = __builtin_amdgcn_perm(v[1][r >> 1], v[0][r >> 1], sel);
+      o.y = __builtin_amdgcn_perm(v[3][r >> 1], v[2][r >> 1], sel);
+      o.z = __builtin_amdgcn_perm(v[5][r >> 1], v[4][r >> 1], sel);
+      o.w = __builtin_amdgcn_perm(v[7][r >> 1], v[6][r >> 1], sel);
+      *reinterpret_cast<u32x4*>(lds_tile + lds_chunk(rg * 8 + r, kg)) = o;
     }
   }
 }
@@ -87,7 +111,7 @@ template <int MODE, int DT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
     const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kStages * 2 * kTileBytes];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   typedef typename Elem16<DT>::vec8 vec8;
 
   // ---- which tile ---------------------------------------------------------------------------------
@@ -95,9 +119,19 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   int expert = 0, row0 = 0, rows = 0, col0 = 0, m0 = 0;
   Operand opA, opB;   // opA: the operand whose tile rows are the output rows; opB: the output columns
   int kt_count = 0;
+  // Consecutive block ids land on different XCDs (round robin over 8): remap so that each XCD works on
+  // a contiguous run of the tile list and its L2 sees the same panels from many CUs.
+  auto xcd_tile = [](int bid, int total) {
+    const int per = (total + 7) >> 3;
+    const int t = (bid & 7) * per + (bid >> 3);
+    return ((bid >> 3) < per && t < total) ? t : -1;
+  };
   if (MODE == 0) {
     // tiles ordered expert-major, then n-tile, then m-tile; blocks past the last tile leave
-    int tile = blockIdx.x;
+    int total = 0;
+    for (int i = 0; i < n_exp; ++i) total += (offsets[i + 1] - offsets[i] + BM - 1) / BM * n_tiles;
+    int tile = xcd_tile(blockIdx.x, total);
+    if (tile < 0) return;
     bool found = false;
     int lo = offsets[0];
     for (int i = 0; i < n_exp && !found; ++i) {
@@ -122,7 +156,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
     kt_count = (K + BK - 1) / BK;
   } else {
     const int m_tiles = (M + BM - 1) / BM;
-    int tile = blockIdx.x;
+    int tile = xcd_tile(blockIdx.x, n_exp * m_tiles * n_tiles);
+    if (tile < 0) return;
     expert = tile / (m_tiles * n_tiles);
     tile -= expert * m_tiles * n_tiles;
     const int mt = tile / n_tiles, nt = tile - mt * n_tiles;
@@ -136,11 +171,14 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
     kt_count = (hi - lo + BK - 1) / BK;
   }
   constexpr bool kAContig = MODE == 0;   // A[r, k]: k contiguous only for the data gradient
-  constexpr bool kBContig = false;       // B's k always runs along memory rows
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int frow = lane & 31, half = lane >> 5;
+  // staging: wavefronts 0, 1 bring in the A tile, 2, 3 the B tile
+  const bool stage_b = wave >= 2;
+  const int stage_half = wave & 1;
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -150,40 +188,40 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  u32x4 ga[2], gb[2];
+  u32x4 g[8];
+  auto load = [&](int kt) {
+    if (stage_b) load_tile<false>(opB, kt * BK, stage_half, lane, g);
+    else load_tile<kAContig>(opA, kt * BK, stage_half, lane, g);
+  };
+  auto store = [&](unsigned char* buf) {
+    if (stage_b) store_tile<false>(buf + kTileBytes, stage_half, lane, g);
+    else store_tile<kAContig>(buf, stage_half, lane, g);
+  };
   if (kt_count > 0) {
-    load_tile<kAContig>(opA, 0, ga);
-    load_tile<kBContig>(opB, 0, gb);
-    store_tile<kAContig>(lds, ga);
-    store_tile<kBContig>(lds + kTileBytes, gb);
+    load(0);
+    store(lds);
   }
   __syncthreads();
   for (int kt = 0; kt < kt_count; ++kt) {
     unsigned char* cur = lds + (kt & 1) * (2 * kTileBytes);
     unsigned char* nxt = lds + ((kt + 1) & 1) * (2 * kTileBytes);
-    if (kt + 1 < kt_count) {
-      load_tile<kAContig>(opA, (kt + 1) * BK, ga);
-      load_tile<kBContig>(opB, (kt + 1) * BK, gb);
-    }
+    if (kt + 1 < kt_count) load(kt + 1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < 4; ++ks) {
       vec8 fa[2], fb[2];
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
-        fa[mi] = *reinterpret_cast<const vec8*>(cur + (wm * 64 + mi * 32 + frow) * kRowBytes + ks * 32 + half * 16);
+        fa[mi] = *reinterpret_cast<const vec8*>(cur + lds_chunk(wm * 64 + mi * 32 + frow, ks * 2 + half));
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        fb[ni] = *reinterpret_cast<const vec8*>(cur + kTileBytes + (wn * 64 + ni * 32 + frow) * kRowBytes + ks * 32 + half * 16);
+        fb[ni] = *reinterpret_cast<const vec8*>(cur + kTileBytes + lds_chunk(wn * 64 + ni * 32 + frow, ks * 2 + half));
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
           acc[mi][ni] = Elem16<DT>::mfma32(fb[ni], fa[mi], acc[mi][ni]);   // D[n][m]: lane = row m, registers = columns n
     }
-    if (kt + 1 < kt_count) {
-      store_tile<kAContig>(nxt, ga);
-      store_tile<kBContig>(nxt + kTileBytes, gb);
-    }
+    if (kt + 1 < kt_count) store(nxt);
     __syncthreads();
   }
 
@@ -217,39 +255,57 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   }
 }
 
-// H = GeLU(U) and dU = dH * GeLU'(U), elementwise over the packed rows [0, offsets[n_exp]) x F; dH and
-// dU may be the same buffer.  tanh form:  s = 1 / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3):
-// GeLU = u s,   GeLU' = s + 2 u s (1 - s) sqrt(2/pi) (1 + 3 * 0.044715 u^2).
+// H = GeLU(U) and dU = dH * GeLU'(U) over the packed rows [0, offsets[n_exp]) x F, one row per block
+// iteration; dH and dU may be the same buffer.  tanh form:  s = 1 / (1 + exp(-2 z)),
+// z = sqrt(2/pi) (u + 0.044715 u^3):   GeLU = u s,   GeLU' = s + 2 u s (1 - s) sqrt(2/pi) (1 + 3 * 0.044715 u^2).
+// row_dot (may be NULL): row_dot[r] = sum_f dH[r, f] * H[r, f], the derivative with respect to a
+// scale factor of the row's expert output (what the gate weight's gradient is made of), added up in a
+// fixed order (butterfly inside a wavefront, wavefronts in order).
 template <int DT>
 __global__ __launch_bounds__(256) void act_backward_kernel(const bf16_t* __restrict__ U, const bf16_t* dH,
                                                            bf16_t* __restrict__ H, bf16_t* dU,
+                                                           float* __restrict__ row_dot,
                                                            const int32_t* __restrict__ offsets, int n_exp,
                                                            int F) {
-  const int64_t total = static_cast<int64_t>(offsets[n_exp]) * F / 8;   // 16-byte pieces
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const u32x4 u4 = reinterpret_cast<const u32x4*>(U)[i];
-    const u32x4 g4 = reinterpret_cast<const u32x4*>(dH)[i];
-    const uint32_t uw[4] = {u4.x, u4.y, u4.z, u4.w}, gw[4] = {g4.x, g4.y, g4.z, g4.w};
-    uint32_t hw[4], dw[4];
+  __shared__ float part[4];
+  const int rows = offsets[n_exp];
+  const int pieces = F / 8;   // 16-byte pieces per row
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    float dot = 0.f;
+    for (int i = threadIdx.x; i < pieces; i += 256) {
+      const int64_t at = static_cast<int64_t>(r) * pieces + i;
+      const u32x4 u4 = reinterpret_cast<const u32x4*>(U)[at];
+      const u32x4 g4 = reinterpret_cast<const u32x4*>(dH)[at];
+      const uint32_t uw[4] = {u4.x, u4.y, u4.z, u4.w}, gw[4] = {g4.x, g4.y, g4.z, g4.w};
+      uint32_t hw[4], dw[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float u[2], g[2], h[2], du[2];
-      Elem16<DT>::widen2(uw[j], u[0], u[1]);
-      Elem16<DT>::widen2(gw[j], g[0], g[1]);
+      for (int j = 0; j < 4; ++j) {
+        float u[2], g[2], h[2], du[2];
+        Elem16<DT>::widen2(uw[j], u[0], u[1]);
+        Elem16<DT>::widen2(gw[j], g[0], g[1]);
 #pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const float z2 = 1.5957691216057308f * u[e] * fmaf(0.044715f * u[e], u[e], 1.0f);   // 2 z
-        const float s = 1.0f / (1.0f + __expf(-z2));
-        h[e] = u[e] * s;
-        const float dz2 = 1.5957691216057308f * fmaf(3.0f * 0.044715f * u[e], u[e], 1.0f);  // d(2 z)/du
-        du[e] = g[e] * (s + h[e] * (1.0f - s) * dz2);
+        for (int e = 0; e < 2; ++e) {
+          const float z2 = 1.5957691216057308f * u[e] * fmaf(0.044715f * u[e], u[e], 1.0f);   // 2 z
+          const float sg = 1.0f / (1.0f + __expf(-z2));
+          h[e] = u[e] * sg;
+          const float dz2 = 1.5957691216057308f * fmaf(3.0f * 0.044715f * u[e], u[e], 1.0f);  // d(2 z)/du
+          du[e] = g[e] * (sg + h[e] * (1.0f - sg) * dz2);
+          dot = fmaf(g[e], h[e], dot);
+        }
+        hw[j] = Elem16<DT>::pack2(h[0], h[1]);
+        dw[j] = Elem16<DT>::pack2(du[0], du[1]);
       }
-      hw[j] = Elem16<DT>::pack2(h[0], h[1]);
-      dw[j] = Elem16<DT>::pack2(du[0], du[1]);
+      reinterpret_cast<u32x4*>(H)[at] = u32x4{hw[0], hw[1], hw[2], hw[3]};
+      reinterpret_cast<u32x4*>(dU)[at] = u32x4{dw[0], dw[1], dw[2], dw[3]};
     }
-    reinterpret_cast<u32x4*>(H)[i] = u32x4{hw[0], hw[1], hw[2], hw[3]};
-    reinterpret_cast<u32x4*>(dU)[i] = u32x4{dw[0], dw[1], dw[2], dw[3]};
+    if (row_dot != nullptr) {   // (uniform)
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+      if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
+      __syncthreads();
+      if (threadIdx.x == 0) row_dot[r] = ((part[0] + part[1]) + part[2]) + part[3];
+      __syncthreads();
+    }
   }
 }
 
@@ -264,7 +320,7 @@ size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows) {
 hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
                                       const int32_t* offsets, const void* W1, const void* W2,
                                       const void* dY, void* dX, float* dW1, float* dW2, void* scratch,
-                                      hipStream_t s) {
+                                      hipStream_t s, float* row_dot) {
   using namespace bwd;
   // (rows == 0: no packed row can exist; every launch below is then empty except the two weight
   // gradients, whose tiles store zeros)
@@ -286,28 +342,39 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
 
   auto dgrad_grid = [&](int n_out) {
     const int64_t m_tiles = (rows + BM - 1) / BM + N;   // upper bound on the sum of the ceilings
-    return static_cast<unsigned>(m_tiles * ((n_out + BN - 1) / BN));
+    return static_cast<unsigned>((m_tiles * ((n_out + BN - 1) / BN) + 7) / 8 * 8);
   };
   auto wgrad_grid = [&](int m_out, int n_out) {
-    return static_cast<unsigned>(static_cast<int64_t>(N) * ((m_out + BM - 1) / BM) * ((n_out + BN - 1) / BN));
+    return static_cast<unsigned>((static_cast<int64_t>(N) * ((m_out + BM - 1) / BM) * ((n_out + BN - 1) / BN) + 7) / 8 * 8);
   };
-#define PPMOE_BWD(MODE, grid, a, b, cc, m, n, k)                                                       \
-  do {                                                                                                 \
-    if (c.in_dtype == MOE_F16)                                                                         \
-      grouped_gemm_bwd_kernel<MODE, MOE_F16><<<grid, kThreads, 0, s>>>(a, b, cc, offsets, N, m, n, k);  \
-    else                                                                                               \
-      grouped_gemm_bwd_kernel<MODE, MOE_BF16><<<grid, kThreads, 0, s>>>(a, b, cc, offsets, N, m, n, k); \
+  static const hipError_t attrs = [] {
+    const void* kernels[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_BF16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_BF16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_F16>),
+                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_F16>)};
+    for (const void* k : kernels) {
+      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+      if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+  }();
+  if (attrs != hipSuccess) return attrs;
+#define PPMOE_BWD(MODE, grid, a, b, cc, m, n, k)                                                               \
+  do {                                                                                                         \
+    if (c.in_dtype == MOE_F16)                                                                                 \
+      grouped_gemm_bwd_kernel<MODE, MOE_F16><<<grid, kThreads, kLdsBytes, s>>>(a, b, cc, offsets, N, m, n, k);  \
+    else                                                                                                       \
+      grouped_gemm_bwd_kernel<MODE, MOE_BF16><<<grid, kThreads, kLdsBytes, s>>>(a, b, cc, offsets, N, m, n, k); \
   } while (0)
 
   // dH = dY B^T  (into the dU buffer), then H = GeLU(U), dU = dH * GeLU'(U) in place
   PPMOE_BWD(0, dgrad_grid(c.F), dy, w2, dU, 0, c.F, c.d);
   {
-    const int64_t pieces = rows * c.F / 8;
-    const int blocks = static_cast<int>(pieces / 256 + 1 < 256 * 8 ? pieces / 256 + 1 : 256 * 8);
+    const int blocks = static_cast<int>(rows < 256 * 16 ? (rows > 0 ? rows : 1) : 256 * 16);
     if (c.in_dtype == MOE_F16)
-      act_backward_kernel<MOE_F16><<<blocks, 256, 0, s>>>(U, dU, H, dU, offsets, N, c.F);
+      act_backward_kernel<MOE_F16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
     else
-      act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H, dU, offsets, N, c.F);
+      act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
   }
   // dX = dU A^T
   PPMOE_BWD(0, dgrad_grid(c.d), dU, w1, dX, 0, c.d, c.F);
