@@ -180,7 +180,7 @@ __device__ __forceinline__ void score_token(float* lg, int t, int T, int E, int 
   }
 }
 
-// bf16 router: a block owns 16*MT tokens; its 4 wavefronts split d between them (span-interleaved)
+// 16-bit router, direct operand loads (used for more than 64 experts): a block owns 16*MT tokens; its 4 wavefronts split d between them (span-interleaved)
 // and their partial logits are added in wavefront order through LDS, so the float32 sum order is
 // fixed.  MFMA operands come straight from global memory: lane (r = lane%16, g = lane/16) holds 8
 // consecutive k of row r, which is exactly a 16-byte load; four such loads cover 64 contiguous
@@ -279,6 +279,125 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(
   }
 }
 
+// The same router with the token rows read as whole rows: a block brings its 16*MT token rows in
+// through LDS, 2048/MT columns at a time, every wavefront load covering one contiguous kilobyte of a
+// row (the direct operand loads above fetch 64 bytes of each of 16 rows per instruction, which costs
+// a fifth to a quarter of the achievable read bandwidth); the MFMA operands of the tokens then come
+// from LDS (rows 16 bytes apart from a multiple of the bank width: conflict free), those of the
+// router matrix straight from global memory (L2) as above.  The next chunk's rows are in flight, in
+// registers, while the current one is multiplied.  Partial logits of the four wavefronts (which
+// split the columns of a chunk) are added in wavefront order: fixed float32 sum order.
+template <int NT, int MT, int DT>
+__global__ __launch_bounds__(256) void gate_rows_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg, const float* __restrict__ bias,
+    float* __restrict__ logits_out, int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
+    int32_t* __restrict__ seg_count, float* __restrict__ part_prob, int32_t* __restrict__ part_cnt,
+    int T, int d, int E, int k, int renorm, int local_begin, int n_local) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int kTok = 16 * MT;
+  constexpr int kLd = NT * 16 + 1;
+  constexpr int CK = 2048 / MT;               // columns per chunk
+  constexpr int kPiecesRow = CK / 8;          // 16-byte pieces of a row per chunk
+  constexpr int kRowBytes = CK * 2 + 16;      // one token row of a chunk in LDS
+  constexpr int kStepsWave = CK / 32 / 4;     // MFMA steps per wavefront per chunk
+  unsigned char* xt = smem;                                                 // [kTok][kRowBytes]
+  float* red = reinterpret_cast<float*>(smem + kTok * kRowBytes);           // [kTok][kLd]
+  int32_t* picks = reinterpret_cast<int32_t*>(red + kTok * kLd);            // [kTok][k]
+  const bool extras = seg_count != nullptr || part_prob != nullptr;
+  typedef typename Elem16<DT>::vec8 vec8;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  const int n_groups = (T + kTok - 1) / kTok;   // a group of kTok tokens = one segment of the permutation
+  const int n_chunks = (d + CK - 1) / CK;
+
+  // staging: kTok * kPiecesRow = 4096 pieces per chunk, 16 per thread, consecutive threads on
+  // consecutive pieces of a row
+  u32x4 st[16];
+  auto load_chunk = [&](int grp, int ck) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int p = threadIdx.x + 256 * i;
+      const int row = p / kPiecesRow, col = ck * CK + (p % kPiecesRow) * 8;
+      const int t = min(grp * kTok + row, T - 1);
+      st[i] = col < d ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + static_cast<size_t>(t) * d + col)) : zero;
+    }
+  };
+  const bf16_t* wrow[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) wrow[nt] = Wg + static_cast<size_t>(min(nt * 16 + r, E - 1)) * d;
+
+  // The block walks over groups of tokens; the rows of the next chunk -- of this group or of the
+  // block's next one -- are always in flight, also during the softmax / top-k tail.
+  int grp = blockIdx.x;
+  if (grp < n_groups) load_chunk(grp, 0);
+  for (; grp < n_groups; grp += gridDim.x) {
+    const int t0 = grp * kTok;
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ck = 0; ck < n_chunks; ++ck) {
+      // this wavefront's router operands of the chunk (steps wave, wave + 4, ...): on their way first
+      u32x4 b[kStepsWave][NT];
+#pragma unroll
+      for (int j = 0; j < kStepsWave; ++j) {
+        const int col = ck * CK + 32 * (wave + 4 * j) + 8 * g;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          b[j][nt] = col < d ? *reinterpret_cast<const u32x4*>(wrow[nt] + col) : zero;
+      }
+      __syncthreads();   // the previous chunk has been multiplied (and the previous group's tail is over)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int p = threadIdx.x + 256 * i;
+        *reinterpret_cast<u32x4*>(xt + (p / kPiecesRow) * kRowBytes + (p % kPiecesRow) * 16) = st[i];
+      }
+      __syncthreads();
+      if (ck + 1 < n_chunks) load_chunk(grp, ck + 1);
+      else if (grp + static_cast<int>(gridDim.x) < n_groups) load_chunk(grp + gridDim.x, 0);
+#pragma unroll
+      for (int j = 0; j < kStepsWave; ++j) {
+        const int off = (32 * (wave + 4 * j) + 8 * g) * 2;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const vec8 a = *reinterpret_cast<const vec8*>(xt + (mt * 16 + r) * kRowBytes + off);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[mt][nt] = Elem16<DT>::mfma16(a, __builtin_bit_cast(vec8, b[j][nt]), acc[mt][nt]);
+        }
+      }
+    }
+
+    // D layout of the 16x16 MFMA: lane holds column (lane % 16), rows (lane / 16) * 4 + i.
+    for (int w = 0; w < 4; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              float* p = &red[(mt * 16 + g * 4 + i) * kLd + nt * 16 + r];
+              *p = (w == 0) ? acc[mt][nt][i] : (*p + acc[mt][nt][i]);
+            }
+      }
+      __syncthreads();
+    }
+    if (threadIdx.x < kTok)
+      score_token<(NT <= 4 ? NT * 16 : 0)>(&red[threadIdx.x * kLd], t0 + threadIdx.x, T, E, k, renorm, bias,
+                                           logits_out, expert_idx, gate_w, picks + threadIdx.x * k, extras,
+                                           part_prob != nullptr);
+    if (extras) {
+      __syncthreads();
+      block_segment_sums(red, kLd, picks, kTok, k, E, local_begin, n_local, grp, n_groups, seg_count,
+                         part_prob, part_cnt);
+    }
+  }
+}
+
 // float32 router (the small parity configuration): one wavefront per token, experts four at a time,
 // fixed butterfly reduction order.
 __global__ __launch_bounds__(256) void gate_f32_kernel(
@@ -336,9 +455,46 @@ __global__ __launch_bounds__(256) void gate_from_logits_kernel(
 }
 
 template <int NT, int MT>
-static void launch_bf16(const moe_config& c, const void* x, const void* Wg, const float* bias,
-                        float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s,
-                        GateFusion* fusion) {
+static hipError_t launch_bf16(const moe_config& c, const void* x, const void* Wg, const float* bias,
+                              float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s,
+                              GateFusion* fusion) {
+  constexpr int kTok = 16 * MT;
+  constexpr size_t lds = kTok * (2048 / MT * 2 + 16) + kTok * (NT * 16 + 1) * sizeof(float) +
+                         kTok * kMaxTopK * sizeof(int32_t);
+  static bool attr_set = false;   // (an idempotent attribute: a race between two first calls is harmless)
+  if (!attr_set) {
+    const void* kernels[] = {reinterpret_cast<const void*>(gate_rows_kernel<NT, MT, MOE_BF16>),
+                             reinterpret_cast<const void*>(gate_rows_kernel<NT, MT, MOE_F16>)};
+    for (const void* kern : kernels) {
+      hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+  }
+  const int n_groups = (c.T + kTok - 1) / kTok;
+  const int blocks = n_groups < 512 ? n_groups : 512;   // two resident blocks per compute unit walk over the groups
+#define PPMOE_GATE(DT)                                                                                 \
+  gate_rows_kernel<NT, MT, DT><<<blocks, 256, lds, s>>>(                                               \
+      static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(Wg), bias, logits_out, expert_idx,     \
+      gate_w, fusion != nullptr ? fusion->seg_count : nullptr,                                         \
+      fusion != nullptr ? fusion->part_prob : nullptr, fusion != nullptr ? fusion->part_cnt : nullptr, \
+      c.T, c.d, c.E, c.top_k, c.renorm_topk, c.local_begin, c.local_count)
+  if (c.in_dtype == MOE_F16) PPMOE_GATE(MOE_F16);
+  else PPMOE_GATE(MOE_BF16);
+#undef PPMOE_GATE
+  if (fusion != nullptr) {
+    fusion->seg_assign = kTok * c.top_k;
+    fusion->n_seg = n_groups;
+  }
+  return hipGetLastError();
+}
+
+// The direct-operand kernel (more than 64 experts: the whole-row kernel's register budget does not
+// reach that far).
+template <int NT, int MT>
+static hipError_t launch_bf16_direct(const moe_config& c, const void* x, const void* Wg, const float* bias,
+                                     float* logits_out, int32_t* expert_idx, float* gate_w, hipStream_t s,
+                                     GateFusion* fusion) {
   int blocks = (c.T + 16 * MT - 1) / (16 * MT);
 #define PPMOE_GATE(DT)                                                                                 \
   gate_bf16_kernel<NT, MT, DT><<<blocks, 256, 0, s>>>(                                                 \
@@ -353,6 +509,7 @@ static void launch_bf16(const moe_config& c, const void* x, const void* Wg, cons
     fusion->seg_assign = 16 * MT * c.top_k;
     fusion->n_seg = blocks;
   }
+  return hipGetLastError();
 }
 
 // Can launch_gate honour a GateFusion request for this configuration?  (The 16-bit router kernel can.)
@@ -376,12 +533,15 @@ hipError_t launch_gate(const moe_config& c, const void* x, const void* Wg, const
                                                   c.renorm_topk);
     return hipGetLastError();
   }
-  if (c.E <= 16) launch_bf16<1, 1>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
-  else if (c.E <= 32) launch_bf16<2, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
-  else if (c.E <= 64) launch_bf16<4, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
-  else if (c.E <= 128) launch_bf16<8, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
-  else launch_bf16<16, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
-  return hipGetLastError();
+  // Up to 16 experts: more tokens per block where that still leaves two blocks per compute unit -- the
+  // router rows, fetched once per block, then cost a half or a quarter of the L2 -> CU traffic.
+  if (c.E <= 16 && c.T >= 64 * 512) return launch_bf16<1, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  if (c.E <= 16 && c.T >= 32 * 512) return launch_bf16<1, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  if (c.E <= 16) return launch_bf16<1, 1>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  if (c.E <= 32) return launch_bf16<2, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  if (c.E <= 64) return launch_bf16<4, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  if (c.E <= 128) return launch_bf16_direct<8, 4>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
+  return launch_bf16_direct<16, 2>(c, x, Wg, bias, logits_out, expert_idx, gate_w, s, fusion);
 }
 
 }  // namespace ppmoe

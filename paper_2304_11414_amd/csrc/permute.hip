@@ -110,33 +110,43 @@ __global__ __launch_bounds__(256) void segment_count_kernel(const int32_t* __res
     count_segment(expert_idx, seg_count, seg, n_assign, n_seg, seg_assign, local_begin, n_local);
 }
 
-// Step 2.  One wavefront per local expert: seg_base = exclusive scan of seg_count over segments
-// (may be done in place), totals[i] = queue length of expert i before any capacity clamp.
+// Step 2.  One block per local expert: seg_base = exclusive scan of seg_count over segments (may be
+// done in place), totals[i] = queue length of expert i before any capacity clamp.  A thread adds up a
+// run of consecutive segments, the 256 run sums are scanned (butterfly inside a wavefront, the four
+// wavefront totals in order), and every thread then writes the prefixes of its run.
+constexpr int kScanThreads = 256;
 __device__ __forceinline__ void scan_expert(const int32_t* seg_count, int32_t* seg_base,
                                             int32_t* totals, int i, int n_seg) {
-  const int lane = lane_id();
+  __shared__ int wave_total[4];
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int32_t* in = seg_count + static_cast<int64_t>(i) * n_seg;
   int32_t* out = seg_base + static_cast<int64_t>(i) * n_seg;
-  int carry = 0;
-  for (int s0 = 0; s0 < n_seg; s0 += kWave) {
-    int s = s0 + lane;
-    int v = s < n_seg ? in[s] : 0;
-    int incl = v;
+  const int run = (n_seg + kScanThreads - 1) / kScanThreads;
+  const int s0 = threadIdx.x * run, s1 = min(n_seg, s0 + run);
+  int sum = 0;
+  for (int s = s0; s < s1; ++s) sum += in[s];
+  int incl = sum;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      int up = __shfl_up(incl, off, 64);
-      if (lane >= off) incl += up;
-    }
-    if (s < n_seg) out[s] = carry + incl - v;
-    carry += __shfl(incl, kWave - 1, 64);
+  for (int off = 1; off < kWave; off <<= 1) {
+    int up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
   }
-  if (lane == 0) totals[i] = carry;
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  __syncthreads();
+  int before = incl - sum;
+  for (int w = 0; w < wave; ++w) before += wave_total[w];
+  for (int s = s0; s < s1; ++s) {
+    const int v = in[s];
+    out[s] = before;
+    before += v;
+  }
+  if (threadIdx.x == kScanThreads - 1) totals[i] = before;
 }
 
 // Blocks 0 .. n_local-1 scan one expert each.  One more block, when the gating kernel has left
 // per-segment partial sums for the balance loss (Algorithm 1's l_aux; see aux.hip for the formula),
 // adds them up in segment order (fixed order: bitwise reproducible) and writes the loss.
-__global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
+__global__ __launch_bounds__(kScanThreads) void segment_scan_kernel(const int32_t* __restrict__ seg_count,
                                                           int32_t* __restrict__ seg_base,
                                                           int32_t* __restrict__ totals, int n_seg,
                                                           int n_local, AuxOut aux) {
@@ -145,8 +155,7 @@ __global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restr
     return;
   }
   __shared__ float term[kMaxExperts];
-  const int lane = lane_id();
-  for (int e = lane; e < aux.E; e += kWave) {
+  for (int e = threadIdx.x; e < aux.E; e += kScanThreads) {
     float prob = 0.f;
     int cnt = 0;
     for (int g = 0; g < aux.n_part; ++g) {
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(64) void segment_scan_kernel(const int32_t* __restr
     term[e] = aux.T > 0 ? mp * (static_cast<float>(cnt) / static_cast<float>(aux.T)) : 0.f;
   }
   __syncthreads();
-  if (lane == 0) {
+  if (threadIdx.x == 0) {
     float sum = 0.f;
     for (int e = 0; e < aux.E; ++e) sum += term[e];   // ascending expert order
     *aux.l_aux = static_cast<float>(aux.E) * sum;
@@ -257,7 +266,7 @@ hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* exper
                                                 c.local_begin, N);
   AuxOut no_aux = {};
   const bool with_aux = aux != nullptr && aux->l_aux != nullptr;
-  segment_scan_kernel<<<N + (with_aux ? 1 : 0), 64, 0, s>>>(seg_count, seg_base, totals, n_seg, N,
+  segment_scan_kernel<<<N + (with_aux ? 1 : 0), kScanThreads, 0, s>>>(seg_count, seg_base, totals, n_seg, N,
                                                             with_aux ? *aux : no_aux);
   if (blocks > 0) {
     rank_kernel<<<blocks, 256, 0, s>>>(expert_idx, seg_base, totals, counts, offsets, perm,
