@@ -80,6 +80,10 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into synth.CONFIGS (1 = headline)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", choices=("bf16", "f16"), default=None,
+                    help="run the (bf16) workload in this 16-bit type instead (f16: the paper's own precision)")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip the (untimed-region) measurement of moe_layer_backward")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (reference of known "
                          "traffic for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
@@ -97,12 +101,15 @@ def main():
     B.load_library()
     B.moe_init()          # one-time set-up of the device (the only call here that synchronises by itself)
     lc = synth.CONFIGS[args.config]
+    if args.dtype is not None and lc.in_dtype != "f32" and args.dtype != lc.in_dtype:
+        lc = lc.scaled(name=f"{lc.name}_{args.dtype}", in_dtype=args.dtype,
+                       out_dtype=args.dtype if lc.out_dtype != "f32" else "f32")
     log(f"[bench] workload {lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
         f"top_k={lc.top_k} cf={lc.capacity_factor} {lc.in_dtype}->{lc.out_dtype}")
     inp = synth.make_inputs(lc)
     cfg = B.config_from(lc)
-    tdt = torch.bfloat16 if lc.in_dtype == "bf16" else torch.float32
-    odt = torch.bfloat16 if lc.out_dtype == "bf16" else torch.float32
+    tmap = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+    tdt, odt = tmap[lc.in_dtype], tmap[lc.out_dtype]
     dev = {k: (torch.from_numpy(v).cuda().to(tdt) if k != "bias" else torch.from_numpy(v).cuda())
            for k, v in inp.items() if v is not None}
     bias = dev.get("bias")
@@ -240,8 +247,8 @@ def main():
 
     counts = views["counts"].cpu().numpy()
     A = int(views["offsets"][-1].item())
-    eb = 2 if lc.in_dtype == "bf16" else 4
-    ob = 2 if lc.out_dtype == "bf16" else 4
+    eb = 4 if lc.in_dtype == "f32" else 2
+    ob = 4 if lc.out_dtype == "f32" else 2
     k = lc.top_k
     flops_up = 2.0 * A * lc.d * lc.F
     flops_dn = 2.0 * A * lc.F * lc.d
@@ -274,11 +281,47 @@ def main():
         "slice_frac_of_hbm_peak": round(bytes_slice / (standalone_ms["slice"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         "combine_frac_of_hbm_peak": round(bytes_combine / (standalone_ms["combine"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
     }
-    log("[bench] " + json.dumps(detail))
     # The dominant kernel is whichever of the two grouped GEMMs (same kernel template, equal FLOPs)
-    # takes longer.
+    # takes longer.  Which roof bounds it: the matrix cores, unless streaming the local experts' weights
+    # once from HBM already takes longer than the FLOPs at peak (few rows per expert: workload 4).
     dom = "ffn_up" if st["ffn_up"] >= st["ffn_down"] else "ffn_down"
     dom_tflops = tflops_up if dom == "ffn_up" else tflops_dn
+    gemm_bytes = lc.n_local * lc.d * lc.F * eb + A * (lc.d + lc.F) * eb      # weights once + both activations
+    t_mfma = flops_up / (PEAK_BF16_TFLOPS * 1e12)
+    t_hbm = gemm_bytes / (PEAK_HBM_GBS * 1e9)
+    detail["gemm_roof"] = {"flops_per_gemm": flops_up, "bytes_per_gemm": gemm_bytes,
+                           "time_at_mfma_peak_us": round(t_mfma * 1e6, 2), "time_at_hbm_peak_us": round(t_hbm * 1e6, 2),
+                           "ffn_up_frac_of_roof": round(max(t_mfma, t_hbm) / (st["ffn_up"] * 1e-3), 4),
+                           "ffn_down_frac_of_roof": round(max(t_mfma, t_hbm) / (st["ffn_down"] * 1e-3), 4)}
+    if t_hbm > t_mfma:
+        dom_gbs = gemm_bytes / (st[dom] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": f"grouped_gemm_bf16_fast_kernel ({dom})", "achieved": dom_gbs,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dom_gbs / PEAK_HBM_GBS,
+                    "traffic": measured_traffic(lc.name, dom)}
+    else:
+        roofline = {"bound": "mfma", "kernel": f"grouped_gemm_bf16_fast_kernel ({dom})", "achieved": dom_tflops,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS,
+                    "traffic": measured_traffic(lc.name, dom)}
+
+    # The layer's backward (a NEXT row of the scope, outside the timed forward regions): a few calls,
+    # timed with events; its five grouped GEMMs are 2.5 x the forward's FLOPs.
+    if lc.in_dtype != "f32" and not args.no_backward:
+        try:
+            d_out = torch.randn((lc.T, lc.d), device="cuda").to(odt)
+            dx = torch.empty((lc.T, lc.d), dtype=tdt, device="cuda")
+            dWg = torch.empty((lc.E, lc.d), dtype=torch.float32, device="cuda")
+            dW1 = torch.empty((lc.n_local, lc.F, lc.d), dtype=torch.float32, device="cuda")
+            dW2 = torch.empty((lc.n_local, lc.d, lc.F), dtype=torch.float32, device="cuda")
+            bws = torch.empty(B.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+            bw_ms = timed(lambda: B.moe_layer_backward(cfg, dev["x"], dev["Wg_t"], bias, dev["W1_t"], dev["W2_t"],
+                                                       d_out, dx, dWg, None, dW1, dW2, bws), 5)
+            detail["backward"] = {"ms_per_call": round(bw_ms, 4),
+                                  "gemm_tflops": round(5 * flops_up / (bw_ms * 1e-3) / 1e12, 1),
+                                  "ratio_to_forward": round(bw_ms / ms_per_step, 2)}
+            del d_out, dx, dWg, dW1, dW2, bws
+        except Exception as exc:   # (the backward is not part of the headline number)
+            log(f"[bench] backward not measured: {exc!r}")
+    log("[bench] " + json.dumps(detail))
 
     result = {
         "metric": "MoE-layer fwd tokens/s at d=2048,E=8,top-1 bf16; % MFMA peak (GEMM), % HBM (slice)",
@@ -292,9 +335,7 @@ def main():
         "config": {"workload": f"{lc.name}: T={lc.T} d={lc.d} F={lc.F} E={lc.E} local={lc.n_local} "
                                f"top_k={lc.top_k} capacity_factor={lc.capacity_factor} "
                                f"{lc.in_dtype} in / {lc.out_dtype} out, seed {lc.seed}"},
-        "roofline": {"bound": "mfma", "kernel": f"grouped_gemm_bf16_fast_kernel ({dom})",
-                     "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": measured_traffic(lc.name, dom)},
+        "roofline": roofline,
         "detail": detail,
     }
     if not args.no_cpu_baseline:
