@@ -243,6 +243,34 @@ def main():
     standalone_ms = {
         "slice": timed_graph(lambda st: B.moe_slice_rows(cfg, dev["x"], views["perm"], views["offsets"], xs, stream=st)),
         "combine": timed_graph(lambda st: B.moe_combine(cfg, ys, views["inv_perm"], views["gate_w"], out2, stream=st))}
+    # What clock the two GEMMs run at (the library's in-kernel read-out), each launched alone a few
+    # times on the layer's routing; and, for context, the vendor library's dense GEMM (torch.matmul)
+    # on the same two shapes with all rows in one group -- no ragged groups, no activation.
+    gemm_clock, dense = {}, {}
+    if lc.in_dtype != "f32" and int(views["offsets"][-1].item()) > 0:
+        rows_now = int(views["offsets"][-1].item())
+        Hs = torch.empty((rows_max, lc.F), dtype=tdt, device="cuda")
+        fws = torch.empty(B.moe_ffn_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+        for name, call in (("ffn_up", lambda: B.moe_expert_ffn_up(cfg, xs, views["offsets"], dev["W1_t"], Hs, fws)),
+                           ("ffn_down", lambda: B.moe_expert_ffn_down(cfg, Hs, views["offsets"], dev["W2_t"], ys, fws))):
+            ms = timed(call, 5)
+            ghz, us = B.moe_ffn_clock(cfg, fws, False)
+            gemm_clock[name] = {"shader_ghz": round(ghz, 3), "first_block_us": round(us, 1), "alone_ms": round(ms, 5)}
+        assert B.moe_ffn_check(cfg, fws, False) == 0
+        del Hs, fws
+        a_up = torch.randn((rows_now, lc.d), device="cuda").to(tdt)
+        w_up = (torch.randn((lc.F, lc.d), device="cuda") * 0.02).to(tdt)
+        ms_up = timed(lambda: torch.matmul(a_up, w_up.t()), 10)
+        del a_up
+        a_dn = torch.randn((rows_now, lc.F), device="cuda").to(tdt)
+        w_dn = w_up.view(lc.d, lc.F)                            # (same layout as W2[i]: [d, F], F contiguous)
+        ms_dn = timed(lambda: torch.matmul(a_dn, w_dn.t()), 10)
+        del a_dn, w_up, w_dn
+        fl = 2.0 * rows_now * lc.d * lc.F
+        dense = {"what": "torch.matmul (vendor BLAS), one dense group of all kept rows, no activation",
+                 "up_ms": round(ms_up, 5), "down_ms": round(ms_dn, 5),
+                 "up_frac_of_mfma_peak": round(fl / (ms_up * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                 "down_frac_of_mfma_peak": round(fl / (ms_dn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
     del xs, ys, out2
 
     counts = views["counts"].cpu().numpy()
@@ -270,6 +298,8 @@ def main():
         "ffn_frac_of_mfma_peak": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
                                        / 1e12 / PEAK_BF16_TFLOPS, 4),
         "empirical_ceilings": ceilings,
+        "gemm_clock": gemm_clock,
+        "dense_gemm_library": dense,
         "ffn_frac_of_mfma_random_ceiling": round((flops_up + flops_dn) / ((st["ffn_up"] + st["ffn_down"]) * 1e-3)
                                                  / 1e12 / ceilings["mfma_random_tflops"], 4),
         "gate_gbs": round(bytes_gate / (st["gate"] * 1e-3) / 1e9, 1),

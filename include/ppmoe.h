@@ -11,7 +11,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued
  *     asynchronously; nothing here allocates or frees device memory.  Results are valid once the
  *     caller has synchronised the stream.  The calls that SYNCHRONISE the stream are: moe_init;
- *     moe_ffn_check; moe_event_elapsed_ms (on its event); and, once per device and only if moe_init
+ *     moe_ffn_check; moe_ffn_clock; moe_event_elapsed_ms (on its event); and, once per device and only if moe_init
  *     has not been called for that device, the first expert-FFN call (moe_expert_ffn, _up, _down,
  *     moe_layer_forward, moe_expert_ffn_backward) with bf16/fp16 input -- unless that call is made
  *     under stream capture, where nothing synchronises (see moe_init).
@@ -344,6 +344,16 @@ int moe_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
  * clock then settles lower, under the power limit, than with constant operands); `sink`: device
  * memory for 65536 floats (overwritten); `*flops` (host) receives the flop count of the launch. */
 int moe_mfma_probe(int64_t iters, int random_operands, float* sink, double* flops, void* stream);
+
+/* What clock the matrix-core kernels ran at.  The fast path of the grouped GEMMs (Section 3.3.2) leaves
+ * in its scratch the shader-clock and wall-clock counters its first block read at its start and its
+ * end; this reads them back for the LAST such launch on `workspace` (the one given to moe_expert_ffn_*,
+ * or, layer_workspace != 0, to moe_layer_forward) and returns the shader clock in GHz and the
+ * block's lifetime in microseconds (both 0 if no fast-path launch has used the workspace).  A
+ * measurement helper: under load the clock settles well below the 2.4 GHz the published peak is
+ * quoted at, and a fraction of that peak has to be read with this beside it.  Synchronises `stream`. */
+int moe_ffn_clock(const moe_config* cfg, const void* workspace, int layer_workspace, double* shader_ghz,
+                  double* kernel_us, void* stream);
 
 /* Timing helpers: thin wrappers over hipEvent so a caller without HIP headers can time stages.
  * moe_event_elapsed_ms synchronises on `stop` before reading. */

@@ -56,6 +56,7 @@ _PROTOTYPES = {
     "moe_layer_backward_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_layer_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
+    "moe_ffn_clock": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_double), POINTER(c_double), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
     "moe_layer_forward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 7 + [c_size_t, POINTER(c_void_p), c_void_p]),
     "moe_layer_forward_aux": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 10 + [c_size_t, POINTER(c_void_p), c_void_p]),
@@ -245,6 +246,15 @@ def moe_ffn_check(cfg, workspace, layer_workspace, stream=None) -> int:
     _check(load_library().moe_ffn_check(byref(cfg), _ptr(workspace), int(bool(layer_workspace)),
                                         byref(status), _stream(stream)), "moe_ffn_check")
     return status.value
+
+
+def moe_ffn_clock(cfg, workspace, layer_workspace, stream=None):
+    """(shader clock in GHz, lifetime in microseconds) of the first block of the last fast-path GEMM
+    launch on `workspace` (synchronises); (0, 0) if there was none."""
+    ghz, us = c_double(0.0), c_double(0.0)
+    _check(load_library().moe_ffn_clock(byref(cfg), _ptr(workspace), int(bool(layer_workspace)),
+                                        byref(ghz), byref(us), _stream(stream)), "moe_ffn_clock")
+    return ghz.value, us.value
 
 
 def moe_combine(cfg, y_sliced, inv_perm, gate_w, out, stream=None):

@@ -435,6 +435,35 @@ int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_worksp
   return MOE_OK;
 }
 
+int moe_ffn_clock(const moe_config* cfg, const void* workspace, int layer_workspace, double* shader_ghz,
+                  double* kernel_us, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (workspace == nullptr || shader_ghz == nullptr || kernel_us == nullptr) return MOE_ERR_NULL;
+  const unsigned char* ws = static_cast<const unsigned char*>(workspace);
+  if (layer_workspace) {
+    moe_workspace_layout L;
+    size_t total = 0;
+    layout_of(*cfg, &L, &total);
+    ws += L.gemm;
+  }
+  uint64_t shader = 0, wall = 0;
+  if (read_gemm_clock_words(ws, &shader, &wall, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MOE_ERR_HIP;
+  int dev = 0, wall_khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || wall_khz <= 0)
+    return MOE_ERR_HIP;
+  if (wall == 0 || wall > (1ull << 40) || shader > (1ull << 50)) {   // (no fast-path launch has written the words)
+    *shader_ghz = 0.0;
+    *kernel_us = 0.0;
+    return MOE_OK;
+  }
+  *kernel_us = static_cast<double>(wall) / wall_khz * 1e3;
+  *shader_ghz = static_cast<double>(shader) / static_cast<double>(wall) * wall_khz * 1e-6;
+  return MOE_OK;
+}
+
 int moe_combine(const moe_config* cfg, const void* y_sliced, const int32_t* inv_perm,
                 const float* gate_w, void* out, void* stream) {
   int st = check_config(cfg);

@@ -210,6 +210,8 @@ size_t grouped_gemm_fast_workspace_bytes();
 constexpr uint32_t kGemmErrorMagic = 0x4d6f4500u;
 // Copies that word to the host and synchronises the stream.
 hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream_t s);
+hipError_t read_gemm_clock_words(const void* workspace, uint64_t* shader_ticks, uint64_t* wall_ticks,
+                                 hipStream_t s);
 inline size_t grouped_gemm_workspace_bytes() { return grouped_gemm_fast_workspace_bytes(); }
 // Per-device set-up of the fast GEMM (kernel attributes, placement check); synchronises `s` once.
 hipError_t grouped_gemm_fast_init(hipStream_t s);

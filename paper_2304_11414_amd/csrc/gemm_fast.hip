@@ -207,6 +207,9 @@ __device__ __forceinline__ Tile small_tile_at(const int32_t* __restrict__ offset
 // when a hand-over it waited for did not arrive (the first slot may still be unread by its reader).
 constexpr int kSlotFloats = BM * BN;
 constexpr int kSlotsPerBlock = 2;
+// Behind the flags and the error word: four 64-bit words in which block 0 leaves the shader-clock
+// and wall-clock counters at its start and at its end (what clock the launch ran at).
+constexpr int kClockWord = 2 * kMaxPersistentBlocks + 2;   // (32-bit word index in `flags`, 8-byte aligned)
 constexpr int kDefaultSpinLimit = 1 << 17;   // polls of a flag (a few tenths of a second) before giving up
 
 // The XCD (accelerator complex die) this wavefront runs on.
@@ -246,6 +249,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   // word cannot pass for this launch's epoch (the readers poll tens of microseconds from now).
   if (threadIdx.x == 0)
     __hip_atomic_store(flags + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    unsigned long long* cw = reinterpret_cast<unsigned long long*>(flags + kClockWord);
+    cw[0] = clock64();
+    cw[1] = wall_clock64();
+  }
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -812,6 +820,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
       }
     }
   }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    unsigned long long* cw = reinterpret_cast<unsigned long long*>(flags + kClockWord);
+    cw[2] = clock64();
+    cw[3] = wall_clock64();
+  }
 #undef PPMOE_STEP
 #undef PPMOE_WRITE4
 #undef PPMOE_WRITE
@@ -841,8 +854,25 @@ hipError_t read_gemm_error_word(const void* workspace, uint32_t* word, hipStream
   return e;
 }
 
+// Shader-clock and wall-clock ticks block 0 of the last fast-path launch on this workspace counted
+// between its start and its end.  Synchronises the stream.
+hipError_t read_gemm_clock_words(const void* workspace, uint64_t* shader_ticks, uint64_t* wall_ticks,
+                                 hipStream_t s) {
+  const float* slots = static_cast<const float*>(workspace);
+  const uint32_t* flags = reinterpret_cast<const uint32_t*>(
+      slots + static_cast<size_t>(fast::kSlotsPerBlock) * kMaxPersistentBlocks * fast::kSlotFloats);
+  uint64_t w[4] = {0, 0, 0, 0};
+  hipError_t e = hipMemcpyAsync(w, flags + fast::kClockWord, sizeof(w), hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return e;
+  *shader_ticks = w[2] - w[0];
+  *wall_ticks = w[3] - w[1];
+  return hipSuccess;
+}
+
 size_t grouped_gemm_fast_workspace_bytes() {
-  // slots, flags (+1 word: the error word)
+  // slots, flags (+1 word: the error word), and inside the padding the four clock words
   return static_cast<size_t>(fast::kSlotsPerBlock) * kMaxPersistentBlocks * fast::kSlotFloats * sizeof(float) +
          (2 * kMaxPersistentBlocks + 1) * sizeof(uint32_t) + 256;
 }

@@ -767,6 +767,34 @@ def test_aux_loss_on_the_headline_router():
     assert 0.9 < ref["l_aux"] < 1.2      # a near-uniform router sits just above the balanced value 1
 
 
+def test_ffn_clock_reads_back_what_the_gemm_left():
+    """moe_ffn_clock: nothing for a workspace no fast-path launch has used; after a launch a shader
+    clock inside the device's range and a lifetime of the first block that fits inside the launch's
+    event time."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    cfg = B.make_config(2048, 512, 1024, 4, 1)
+    ws = torch.zeros(B.moe_ffn_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    assert B.moe_ffn_clock(cfg, ws, False) == (0.0, 0.0)
+    x = torch.randn(2048, 512, device="cuda").bfloat16()
+    W1 = (torch.randn(4, 1024, 512, device="cuda") * 0.02).bfloat16()
+    H = torch.empty(2048, 1024, device="cuda", dtype=torch.bfloat16)
+    offsets = torch.tensor([0, 500, 1000, 1500, 2048], dtype=torch.int32, device="cuda")
+    B.moe_init()
+    B.moe_expert_ffn_up(cfg, x, offsets, W1, H, ws)      # (first call: set-up not timed)
+    e0, e1 = B.moe_event_create(), B.moe_event_create()
+    B.moe_event_record(e0)
+    B.moe_expert_ffn_up(cfg, x, offsets, W1, H, ws)
+    B.moe_event_record(e1)
+    ghz, us = B.moe_ffn_clock(cfg, ws, False)
+    ms = B.moe_event_elapsed_ms(e0, e1)
+    B.moe_event_destroy(e0)
+    B.moe_event_destroy(e1)
+    assert 0.5 < ghz < 2.6, ghz
+    assert 0.0 < us <= ms * 1e3 + 1.0, (us, ms)
+    assert B.moe_ffn_check(cfg, ws, False) == 0
+
+
 def test_ffn_check_reads_and_clears_the_error_word():
     """moe_ffn_check reports the word the GEMM kernel would leave (planted from the host here; no
     kernel is made to fail), clears it, and ignores whatever else a recycled workspace holds."""
