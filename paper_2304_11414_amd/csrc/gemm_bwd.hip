@@ -10,7 +10,8 @@
 // and the two weight gradients contract over the packed rows of the expert
 //   dW2[i][c, f] = sum_r dY[r, c] H[r, f],        dW1[i][f, c] = sum_r dU[r, f] X[r, c],
 // so in both an operand reaches the matrix cores across its rows.  One kernel covers the two forms:
-// 128 x 128 x 64 block tile, four wavefronts (2 x 2), each 64 x 64 as 2 x 2 MFMA 32x32x16; operand
+// block tile 256 x 256, 256 x 128 or 128 x 128 (x 64 along k), four wavefronts (2 x 2), each a quarter
+// of the tile as MFMA 32x32x16 blocks; operand
 // tiles go through LDS as [row][k] with k contiguous (rows 144 bytes apart, 16-byte chunks
 // XOR-swizzled: fragment reads and staging writes are free of bank conflicts); an operand whose k
 // runs along memory rows is transposed in registers on its way into LDS (a thread loads an 8 x 8
@@ -18,18 +19,20 @@
 // row).  Weight gradients are float32 (the precision gradients are accumulated in); data gradients
 // have the layer's 16-bit type.  Sums have a fixed order: bitwise reproducible.
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace ppmoe {
 
 namespace bwd {
 
-constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int BK = 64;
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 144;                // one tile row in LDS: 64 k-values (128 bytes) + 16 bytes of skew
-constexpr int kTileBytes = BM * kRowBytes;    // 18 KiB per operand tile
 constexpr int kStages = 2;
-constexpr int kLdsBytes = kStages * 2 * kTileBytes;   // 72 KiB
+// Block tile BM x BN (each 128 or 256): two stages of (BM + BN) rows; 144 KiB for 256 x 256.
+constexpr int lds_bytes(int bm, int bn) { return kStages * (bm + bn) * kRowBytes; }
 
 // Byte offset of 16-byte chunk `ch` (8 k-values) of tile row `row`: chunks are XOR-swizzled with the
 // row's group of 16, so that the eight rows a thread writes after its in-register transpose, 16 rows
@@ -49,19 +52,19 @@ struct Operand {
   int rows, ks;
 };
 
-// One operand tile is 128 rows x 64 k = 1024 chunks of 16 bytes, staged by two wavefronts (half: which
-// of the two), eight chunks per thread.
+// One operand tile is R rows (128 or 256) x 64 k = 8 R chunks of 16 bytes, staged by two wavefronts
+// (half: which of the two), R / 16 chunks per thread.
 //  * k contiguous in memory: lane = (row % 8) * 8 + chunk; eight lanes read one whole 128-byte line.
-//  * rows contiguous in memory: a thread reads an 8 (k) x 8 (rows) block, one 16-byte piece from each
-//    of eight consecutive memory rows (16 lanes read 256 contiguous bytes of each), transposes it in
-//    registers (v_perm_b32) and writes eight 16-byte chunks, one per tile row.
-template <bool K_CONTIGUOUS>
-__device__ __forceinline__ void load_tile(const Operand& op, int k0, int half, int lane, u32x4 (&v)[8]) {
+//  * rows contiguous in memory: a thread reads an 8 (k) x 8 (rows) block per group of 128 rows, one
+//    16-byte piece from each of eight consecutive memory rows (16 lanes read 256 contiguous bytes of
+//    each), transposes it in registers (v_perm_b32) and writes eight 16-byte chunks, one per tile row.
+template <bool K_CONTIGUOUS, int R>
+__device__ __forceinline__ void load_tile(const Operand& op, int k0, int half, int lane, u32x4* v) {
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   if (K_CONTIGUOUS) {
     const int ch = lane & 7;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < R / 16; ++i) {
       const int row = (lane >> 3) + 8 * half + 16 * i;
       const bool ok = row < op.rows && k0 + ch * 8 < op.ks;
       v[i] = ok ? *reinterpret_cast<const u32x4*>(op.base + row * op.ld + k0 + ch * 8) : zero;
@@ -69,56 +72,58 @@ __device__ __forceinline__ void load_tile(const Operand& op, int k0, int half, i
   } else {
     const int rg = lane & 15, kg = half * 4 + (lane >> 4);
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const int k = k0 + kg * 8 + kk;
-      const bool ok = k < op.ks && rg * 8 < op.rows;
-      v[kk] = ok ? *reinterpret_cast<const u32x4*>(op.base + k * op.ld + rg * 8) : zero;
+    for (int g = 0; g < R / 128; ++g) {
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int k = k0 + kg * 8 + kk;
+        const bool ok = k < op.ks && g * 128 + rg * 8 < op.rows;
+        v[g * 8 + kk] = ok ? *reinterpret_cast<const u32x4*>(op.base + k * op.ld + g * 128 + rg * 8) : zero;
+      }
     }
   }
 }
 
-template <bool K_CONTIGUOUS>
-__device__ __forceinline__ void store_tile(unsigned char* lds_tile, int half, int lane, const u32x4 (&v)[8]) {
+template <bool K_CONTIGUOUS, int R>
+__device__ __forceinline__ void store_tile(unsigned char* lds_tile, int half, int lane, const u32x4* v) {
   if (K_CONTIGUOUS) {
     const int ch = lane & 7;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < R / 16; ++i) {
       const int row = (lane >> 3) + 8 * half + 16 * i;
       *reinterpret_cast<u32x4*>(lds_tile + lds_chunk(row, ch)) = v[i];
     }
   } else {
     const int rg = lane & 15, kg = half * 4 + (lane >> 4);
-    // v[kk] dword q holds tile rows 2q (low half) and 2q + 1 (high half) at k = kk; the chunk of tile
-    // row r wants, in dword q, k = 2q (low) and 2q + 1 (high).
+    // v[g * 8 + kk] dword q holds tile rows 2q (low half) and 2q + 1 (high half) at k = kk; the chunk
+    // of tile row r wants, in dword q, k = 2q (low) and 2q + 1 (high).
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      u32x4 o;
-      const uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
-      o.x = __builtin_amdgcn_perm(v[1][r >> 1], v[0][r >> 1], sel);
-      o.y = __builtin_amdgcn_perm(v[3][r >> 1], v[2][r >> 1], sel);
-      o.z = __builtin_amdgcn_perm(v[5][r >> 1], v[4][r >> 1], sel);
-      o.w = __builtin_amdgcn_perm(v[7][r >> 1], v[6][r >> 1], sel);
-      *reinterpret_cast<u32x4*>(lds_tile + lds_chunk(rg * 8 + r, kg)) = o;
+    for (int g = 0; g < R / 128; ++g) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        u32x4 o;
+        const uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
+        o.x = __builtin_amdgcn_perm(v[g * 8 + 1][r >> 1], v[g * 8 + 0][r >> 1], sel);
+        o.y = __builtin_amdgcn_perm(v[g * 8 + 3][r >> 1], v[g * 8 + 2][r >> 1], sel);
+        o.z = __builtin_amdgcn_perm(v[g * 8 + 5][r >> 1], v[g * 8 + 4][r >> 1], sel);
+        o.w = __builtin_amdgcn_perm(v[g * 8 + 7][r >> 1], v[g * 8 + 6][r >> 1], sel);
+        *reinterpret_cast<u32x4*>(lds_tile + lds_chunk(g * 128 + rg * 8 + r, kg)) = o;
+      }
     }
   }
 }
 
-// MODE 0 (data gradient):   C[r, n]    = sum_k A[r, k] * B[i][k, n]   for the rows r of expert i
-//                           A [rows, K] 16-bit, B [n_exp, K, N] 16-bit, C [rows, N] 16-bit
-// MODE 1 (weight gradient): C[i][m, n] = sum_{r in expert i} A[r, m] * B[r, n]
-//                           A [rows, M] 16-bit, B [rows, N] 16-bit, C [n_exp, M, N] float32
-template <int MODE, int DT>
-__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
-    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  typedef typename Elem16<DT>::vec8 vec8;
-
-  // ---- which tile ---------------------------------------------------------------------------------
-  const int n_tiles = (N + BN - 1) / BN;
-  int expert = 0, row0 = 0, rows = 0, col0 = 0, m0 = 0;
+// Which output tile a block computes, and where its operand tiles start.
+struct TileInfo {
+  int expert, row0, rows, col0, m0, kt_count;
   Operand opA, opB;   // opA: the operand whose tile rows are the output rows; opB: the output columns
-  int kt_count = 0;
+};
+
+template <int MODE, int BM, int BN>
+__device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                            const int32_t* __restrict__ offsets, int n_exp, int M, int N,
+                                            int K, TileInfo& ti) {
+  const int n_tiles = (N + BN - 1) / BN;
+  ti.expert = ti.row0 = ti.rows = ti.col0 = ti.m0 = ti.kt_count = 0;
   // Consecutive block ids land on different XCDs (round robin over 8): remap so that each XCD works on
   // a contiguous run of the tile list and its L2 sees the same panels from many CUs.
   auto xcd_tile = [](int bid, int total) {
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
     int total = 0;
     for (int i = 0; i < n_exp; ++i) total += (offsets[i + 1] - offsets[i] + BM - 1) / BM * n_tiles;
     int tile = xcd_tile(blockIdx.x, total);
-    if (tile < 0) return;
+    if (tile < 0) return false;
     bool found = false;
     int lo = offsets[0];
     for (int i = 0; i < n_exp && !found; ++i) {
@@ -140,36 +145,89 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
       const int here = m_tiles * n_tiles;
       if (tile < here) {
         const int nt = tile / m_tiles, mt = tile - nt * m_tiles;
-        expert = i;
-        row0 = lo + mt * BM;
-        rows = min(BM, hi - row0);
-        col0 = nt * BN;
+        ti.expert = i;
+        ti.row0 = lo + mt * BM;
+        ti.rows = min(BM, hi - ti.row0);
+        ti.col0 = nt * BN;
         found = true;
       } else {
         tile -= here;
         lo = hi;
       }
     }
-    if (!found) return;
-    opA = Operand{A + static_cast<int64_t>(row0) * K, K, rows, K};
-    opB = Operand{B + static_cast<int64_t>(expert) * K * N + col0, N, min(BN, N - col0), K};
-    kt_count = (K + BK - 1) / BK;
+    if (!found) return false;
+    ti.opA = Operand{A + static_cast<int64_t>(ti.row0) * K, K, ti.rows, K};
+    ti.opB = Operand{B + static_cast<int64_t>(ti.expert) * K * N + ti.col0, N, min(BN, N - ti.col0), K};
+    ti.kt_count = (K + BK - 1) / BK;
   } else {
     const int m_tiles = (M + BM - 1) / BM;
     int tile = xcd_tile(blockIdx.x, n_exp * m_tiles * n_tiles);
-    if (tile < 0) return;
-    expert = tile / (m_tiles * n_tiles);
-    tile -= expert * m_tiles * n_tiles;
+    if (tile < 0) return false;
+    ti.expert = tile / (m_tiles * n_tiles);
+    tile -= ti.expert * m_tiles * n_tiles;
     const int mt = tile / n_tiles, nt = tile - mt * n_tiles;
-    m0 = mt * BM;
-    col0 = nt * BN;
-    const int lo = offsets[expert], hi = offsets[expert + 1];
-    rows = min(BM, M - m0);
+    ti.m0 = mt * BM;
+    ti.col0 = nt * BN;
+    const int lo = offsets[ti.expert], hi = offsets[ti.expert + 1];
+    ti.rows = min(BM, M - ti.m0);
     // the contraction runs over the expert's packed rows: k = r - lo
-    opA = Operand{A + static_cast<int64_t>(lo) * M + m0, M, rows, hi - lo};
-    opB = Operand{B + static_cast<int64_t>(lo) * N + col0, N, min(BN, N - col0), hi - lo};
-    kt_count = (hi - lo + BK - 1) / BK;
+    ti.opA = Operand{A + static_cast<int64_t>(lo) * M + ti.m0, M, ti.rows, hi - lo};
+    ti.opB = Operand{B + static_cast<int64_t>(lo) * N + ti.col0, N, min(BN, N - ti.col0), hi - lo};
+    ti.kt_count = (hi - lo + BK - 1) / BK;
   }
+  return true;
+}
+
+// Stores a block's accumulators.  A lane holds output row m = lane & 31 of each 32-row block and, in
+// register v, column n = (v / 4) * 8 + (lane >> 5) * 4 + v % 4: four consecutive columns per group.
+template <int MODE, int DT, int BM, int BN>
+__device__ __forceinline__ void store_tile_output(const f32x16 (&acc)[BM / 64][BN / 64], void* __restrict__ C,
+                                                  const TileInfo& ti, int N, int M, int wm, int wn, int frow,
+                                                  int half) {
+  constexpr int MI = BM / 64, NI = BN / 64;
+  const int cols = min(BN, N - ti.col0);
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int m = wm * (BM / 2) + mi * 32 + frow;
+    if (m >= ti.rows) continue;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn * (BN / 2) + ni * 32 + q * 8 + half * 4;
+        if (n >= cols) continue;   // (N is a multiple of 8: a group of 4 columns is all in or all out)
+        const float v0 = acc[mi][ni][q * 4 + 0], v1 = acc[mi][ni][q * 4 + 1];
+        const float v2 = acc[mi][ni][q * 4 + 2], v3 = acc[mi][ni][q * 4 + 3];
+        if (MODE == 0) {
+          bf16_t* c = static_cast<bf16_t*>(C) + static_cast<int64_t>(ti.row0 + m) * N + ti.col0 + n;
+          uint2 p;
+          p.x = Elem16<DT>::pack2(v0, v1);
+          p.y = Elem16<DT>::pack2(v2, v3);
+          *reinterpret_cast<uint2*>(c) = p;
+        } else {
+          float* c = static_cast<float*>(C) + (static_cast<int64_t>(ti.expert) * M + ti.m0 + m) * N + ti.col0 + n;
+          *reinterpret_cast<float4*>(c) = make_float4(v0, v1, v2, v3);
+        }
+      }
+    }
+  }
+}
+
+// MODE 0 (data gradient):   C[r, n]    = sum_k A[r, k] * B[i][k, n]   for the rows r of expert i
+//                           A [rows, K] 16-bit, B [n_exp, K, N] 16-bit, C [rows, N] 16-bit
+// MODE 1 (weight gradient): C[i][m, n] = sum_{r in expert i} A[r, m] * B[r, n]
+//                           A [rows, M] 16-bit, B [rows, N] 16-bit, C [n_exp, M, N] float32
+template <int MODE, int DT, int BM, int BN>
+__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
+    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  typedef typename Elem16<DT>::vec8 vec8;
+
+  TileInfo ti;
+  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti)) return;
+  const Operand opA = ti.opA, opB = ti.opB;
+  const int kt_count = ti.kt_count;
   constexpr bool kAContig = MODE == 0;   // A[r, k]: k contiguous only for the data gradient
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -180,22 +238,26 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   const bool stage_b = wave >= 2;
   const int stage_half = wave & 1;
 
-  f32x16 acc[2][2];
+  constexpr int MI = BM / 64, NI = BN / 64;      // 32 x 32 blocks per wavefront, along m and along n
+  constexpr int kATileBytes = BM * kRowBytes;
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  constexpr int SR = BM > BN ? BM : BN;          // (the staging registers fit the larger operand tile)
+  f32x16 acc[MI][NI];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  u32x4 g[8];
+  u32x4 g[SR / 16];
   auto load = [&](int kt) {
-    if (stage_b) load_tile<false>(opB, kt * BK, stage_half, lane, g);
-    else load_tile<kAContig>(opA, kt * BK, stage_half, lane, g);
+    if (stage_b) load_tile<false, BN>(opB, kt * BK, stage_half, lane, g);
+    else load_tile<kAContig, BM>(opA, kt * BK, stage_half, lane, g);
   };
   auto store = [&](unsigned char* buf) {
-    if (stage_b) store_tile<false>(buf + kTileBytes, stage_half, lane, g);
-    else store_tile<kAContig>(buf, stage_half, lane, g);
+    if (stage_b) store_tile<false, BN>(buf + kATileBytes, stage_half, lane, g);
+    else store_tile<kAContig, BM>(buf, stage_half, lane, g);
   };
   if (kt_count > 0) {
     load(0);
@@ -203,57 +265,268 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   }
   __syncthreads();
   for (int kt = 0; kt < kt_count; ++kt) {
-    unsigned char* cur = lds + (kt & 1) * (2 * kTileBytes);
-    unsigned char* nxt = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+    unsigned char* cur = lds + (kt & 1) * kStageBytes;
+    unsigned char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
     if (kt + 1 < kt_count) load(kt + 1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      vec8 fa[2], fb[2];
+      vec8 fa[MI], fb[NI];
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        fa[mi] = *reinterpret_cast<const vec8*>(cur + lds_chunk(wm * 64 + mi * 32 + frow, ks * 2 + half));
+      for (int mi = 0; mi < MI; ++mi)
+        fa[mi] = *reinterpret_cast<const vec8*>(cur + lds_chunk(wm * (BM / 2) + mi * 32 + frow, ks * 2 + half));
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-        fb[ni] = *reinterpret_cast<const vec8*>(cur + kTileBytes + lds_chunk(wn * 64 + ni * 32 + frow, ks * 2 + half));
+      for (int ni = 0; ni < NI; ++ni)
+        fb[ni] = *reinterpret_cast<const vec8*>(cur + kATileBytes + lds_chunk(wn * (BN / 2) + ni * 32 + frow, ks * 2 + half));
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = Elem16<DT>::mfma32(fb[ni], fa[mi], acc[mi][ni]);   // D[n][m]: lane = row m, registers = columns n
     }
     if (kt + 1 < kt_count) store(nxt);
     __syncthreads();
   }
 
-  // ---- epilogue: lane holds output row m = lane & 31 of each 32-row block and, in register v, column
-  // n = (v / 4) * 8 + (lane >> 5) * 4 + v % 4: four consecutive columns per group.
-  const int cols = min(BN, N - col0);
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
-    const int m = wm * 64 + mi * 32 + frow;
-    if (m >= rows) continue;
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wn * 64 + ni * 32 + q * 8 + half * 4;
-        if (n >= cols) continue;   // (N is a multiple of 8: a group of 4 columns is all in or all out)
-        const float v0 = acc[mi][ni][q * 4 + 0], v1 = acc[mi][ni][q * 4 + 1];
-        const float v2 = acc[mi][ni][q * 4 + 2], v3 = acc[mi][ni][q * 4 + 3];
-        if (MODE == 0) {
-          bf16_t* c = static_cast<bf16_t*>(C) + static_cast<int64_t>(row0 + m) * N + col0 + n;
-          uint2 p;
-          p.x = Elem16<DT>::pack2(v0, v1);
-          p.y = Elem16<DT>::pack2(v2, v3);
-          *reinterpret_cast<uint2*>(c) = p;
-        } else {
-          float* c = static_cast<float*>(C) + (static_cast<int64_t>(expert) * M + m0 + m) * N + col0 + n;
-          *reinterpret_cast<float4*>(c) = make_float4(v0, v1, v2, v3);
-        }
-      }
-    }
-  }
+  store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wm, wn, frow, half);
 }
+
+// The same products on a 256 x 256 x 64 tile with one wavefront per SIMD (256 accumulator registers),
+// software-pipelined by hand, because a single wavefront has nobody to hide its latencies behind:
+//   * two sets of staging registers: a k-tile is loaded a tile and a half before it is written to LDS
+//     (buffer loads whose descriptor ends with the operand's last valid row: tails and phantom tiles
+//     read zeros and the loop has no branches); it is written to the other LDS stage during the first
+//     two k-steps of an iteration (transposed in registers where the contraction index is the memory
+//     row) and the set is reloaded during the last two;
+//   * exactly one LDS or memory instruction after each MFMA: a fragment read after the even ones (the
+//     fragments of k-step s + 1 are read while the MFMAs of k-step s run), a staging write or load
+//     after the odd ones; LDS accesses are inline assembly and every wait is counted by hand (LDS
+//     operations complete in order: "lgkmcnt(n)" lets the n youngest stay outstanding);
+//   * one barrier per k-tile, after the third k-step: by then every wavefront has written its share
+//     of the next stage and read its last fragments of this one; the first fragments of the next
+//     tile are read behind it.
+// The data gradient needs K to be a multiple of 64 (a k-contiguous operand is not masked along k).
+template <int OFF>
+__device__ __forceinline__ void lds_read16_at(u32x4& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ void lds_write16_at(uint32_t addr, const u32x4& v) {
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+#define PPMOE_BWD_TIE8(f) \
+  "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7])
+
+template <int MODE, int DT>
+__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_pipelined_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
+    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
+  constexpr int BM = 256, BN = 256, MI = 4, NI = 4;
+  constexpr int kATileBytes = BM * kRowBytes;
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  typedef typename Elem16<DT>::vec8 vec8;
+
+  TileInfo ti;
+  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti)) return;
+  const int kt_count = ti.kt_count;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int frow = lane & 31, half = lane >> 5;
+  const bool stage_b = wave >= 2;          // wavefronts 0, 1 bring in the A tile, 2, 3 the B tile
+  const int stage_half = wave & 1;
+  const Operand op = stage_b ? ti.opB : ti.opA;
+  const int col_start = stage_b ? ti.col0 : ti.m0;   // (row-contiguous operands: first column of the tile)
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (const __attribute__((address_space(3))) unsigned char*)lds));
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+  // Fragment addresses: row r, 16-byte chunk 2 ks + half, swizzled with (r >> 4) & 7 = 2 i + b for
+  // the i-th 32-row block (b = frow >> 4): chunk 2 (ks ^ i) + (half ^ b), i.e. a per-lane base plus
+  // the constant i * 32 rows + (ks ^ i) * 32 bytes.
+  const int b4 = frow >> 4;
+  const uint32_t fa_addr = lds0 + (wm * 128 + frow) * kRowBytes + ((half ^ b4) << 4);
+  const uint32_t fb_addr = lds0 + kATileBytes + (wn * 128 + frow) * kRowBytes + ((half ^ b4) << 4);
+
+// One MFMA, pinned where it is written (the scheduler may not move anything across it).
+#define PPMOE_BWD_MFMA(f, mi, ni)                                                   \
+  do {                                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                              \
+    acc[mi][ni] = Elem16<DT>::mfma32(__builtin_bit_cast(vec8, f[4 + ni]), __builtin_bit_cast(vec8, f[mi]), acc[mi][ni]); \
+    __builtin_amdgcn_sched_barrier(0);                                              \
+  } while (0)
+#define PPMOE_BWD_WAIT(n, f) asm volatile("s_waitcnt lgkmcnt(" #n ")" : PPMOE_BWD_TIE8(f) : : "memory")
+// fragment i of the A / B tile for k-step NKS, from the stage whose fragment base addresses are fa / fb
+#define PPMOE_BWD_RA(f, i, NKS, fa) lds_read16_at<(i) * 32 * kRowBytes + (((NKS) ^ (i)) << 5)>(f[i], fa)
+#define PPMOE_BWD_RB(f, i, NKS, fb) lds_read16_at<(i) * 32 * kRowBytes + (((NKS) ^ (i)) << 5)>(f[4 + (i)], fb)
+// One k-step: 16 MFMAs on `cur`; after the even ones the eight fragment reads of k-step NKS into `nxt`
+// (order A0 B0 B1 A1 B2 B3 A2 A3, the order in which the MFMAs of the next k-step first need them:
+// MFMAs 0, 0, 1, 2, 4, 5, 8, 10); after the odd ones ODD(0..7).  W0..W10: how many LDS operations
+// may still be outstanding when MFMA 0, 1, 2, 4, 5, 8, 10 issues (-1: nothing to wait for).
+#define PPMOE_BWD_STEP(cur, nxt, NKS, fa, fb, W0, W1, W2, W4, W5, W8, W10, ODD) \
+  do {                                                                         \
+    W0(cur);  PPMOE_BWD_MFMA(cur, 0, 0); PPMOE_BWD_RA(nxt, 0, NKS, fa);         \
+    W1(cur);  PPMOE_BWD_MFMA(cur, 0, 1); ODD(0);                                \
+    W2(cur);  PPMOE_BWD_MFMA(cur, 1, 0); PPMOE_BWD_RB(nxt, 0, NKS, fb);         \
+              PPMOE_BWD_MFMA(cur, 1, 1); ODD(1);                                \
+    W4(cur);  PPMOE_BWD_MFMA(cur, 0, 2); PPMOE_BWD_RB(nxt, 1, NKS, fb);         \
+    W5(cur);  PPMOE_BWD_MFMA(cur, 0, 3); ODD(2);                                \
+              PPMOE_BWD_MFMA(cur, 1, 2); PPMOE_BWD_RA(nxt, 1, NKS, fa);         \
+              PPMOE_BWD_MFMA(cur, 1, 3); ODD(3);                                \
+    W8(cur);  PPMOE_BWD_MFMA(cur, 2, 0); PPMOE_BWD_RB(nxt, 2, NKS, fb);         \
+              PPMOE_BWD_MFMA(cur, 2, 1); ODD(4);                                \
+    W10(cur); PPMOE_BWD_MFMA(cur, 3, 0); PPMOE_BWD_RB(nxt, 3, NKS, fb);         \
+              PPMOE_BWD_MFMA(cur, 3, 1); ODD(5);                                \
+              PPMOE_BWD_MFMA(cur, 2, 2); PPMOE_BWD_RA(nxt, 2, NKS, fa);         \
+              PPMOE_BWD_MFMA(cur, 2, 3); ODD(6);                                \
+              PPMOE_BWD_MFMA(cur, 3, 2); PPMOE_BWD_RA(nxt, 3, NKS, fa);         \
+              PPMOE_BWD_MFMA(cur, 3, 3); ODD(7);                                \
+  } while (0)
+#define PPMOE_BWD_NOWAIT(f) do { } while (0)
+#define PPMOE_BWD_WAIT6(f) PPMOE_BWD_WAIT(6, f)
+#define PPMOE_BWD_WAIT7(f) PPMOE_BWD_WAIT(7, f)
+#define PPMOE_BWD_WAIT8(f) PPMOE_BWD_WAIT(8, f)
+#define PPMOE_BWD_WAIT9(f) PPMOE_BWD_WAIT(9, f)
+#define PPMOE_BWD_WAIT10(f) PPMOE_BWD_WAIT(10, f)
+#define PPMOE_BWD_WAIT11(f) PPMOE_BWD_WAIT(11, f)
+#define PPMOE_BWD_WAIT12(f) PPMOE_BWD_WAIT(12, f)
+#define PPMOE_BWD_WAIT13(f) PPMOE_BWD_WAIT(13, f)
+
+  auto k_loop = [&](auto contig_c) __attribute__((always_inline)) {
+    constexpr bool CONTIG = decltype(contig_c)::value;
+    u32x4 g0[16], g1[16];   // staging set 0: even k-tiles, set 1: odd k-tiles
+    // this lane's byte offset inside a k-tile of its operand, and where it writes in an LDS stage
+    const uint32_t ld2 = static_cast<uint32_t>(op.ld) * 2u;
+    uint32_t loff, st_addr;
+    const int ch = lane & 7;
+    if (CONTIG) {
+      const int lrow = (lane >> 3) + 8 * stage_half;
+      loff = lrow * ld2 + ch * 16;
+      st_addr = lds0 + lrow * kRowBytes;
+    } else {
+      const int rg = lane & 15, kg = stage_half * 4 + (lane >> 4);
+      loff = kg * 8 * ld2 + rg * 16;
+      st_addr = lds0 + (stage_b ? kATileBytes : 0) + rg * 8 * kRowBytes + ((kg ^ (rg >> 1)) << 4);   // rows g * 128 + rg * 8 + r: (row >> 4) & 7 = rg >> 1
+    }
+    // Extent of the operand from the first element of k-tile 0 to the end of its last valid row, and
+    // how much of it a step along k leaves behind: the descriptor of k-tile kt covers what is left,
+    // and nothing at all for a phantom tile (kt >= kt_count): zeros, no memory touched.
+    const int64_t extent0 = CONTIG ? (static_cast<int64_t>(op.rows - 1) * op.ld + op.ks) * 2
+                                   : (static_cast<int64_t>(op.ks) * op.ld - col_start) * 2;
+    const int64_t k_step = CONTIG ? BK * 2 : static_cast<int64_t>(BK) * ld2;
+    auto gload = [&](u32x4 (&g)[16], int kt, int i) __attribute__((always_inline)) {
+      const unsigned char* base = reinterpret_cast<const unsigned char*>(op.base) + kt * k_step;
+      int64_t bytes = extent0 - kt * k_step;
+      bytes = (bytes < 0 || kt >= kt_count) ? 0 : bytes;
+      const int records = static_cast<int>(bytes < 0x7fffffff ? bytes : 0x7fffffff);
+      const __amdgpu_buffer_rsrc_t rsrc =
+          __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base), 0, records, 0x00020000);
+      // CONTIG: rows lrow + 16 i.  Otherwise i = gq * 8 + kk: memory row kg * 8 + kk, columns gq * 128 + rg * 8
+      const uint32_t so = CONTIG ? i * 16 * ld2 : (i & 7) * ld2 + (i >> 3) * 256;
+      g[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, loff, so, 0);
+    };
+    // the i-th of the 16 LDS writes of a staged tile into the stage at byte offset `stage`
+    auto gstore = [&](const u32x4 (&g)[16], uint32_t stage, auto i_c) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_c)::value;
+      if (CONTIG) {
+        lds_write16_at<i * 16 * kRowBytes>(st_addr + stage + ((ch ^ (i & 7)) << 4), g[i]);
+      } else {
+        // g[gq * 8 + kk] dword q holds tile rows 2q (low half) and 2q + 1 (high half) at k = kk; the
+        // chunk of tile row r wants, in dword q, k = 2q (low) and 2q + 1 (high).
+        constexpr int gq = i >> 3, r = i & 7;
+        constexpr uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 o;
+        o.x = __builtin_amdgcn_perm(g[gq * 8 + 1][r >> 1], g[gq * 8 + 0][r >> 1], sel);
+        o.y = __builtin_amdgcn_perm(g[gq * 8 + 3][r >> 1], g[gq * 8 + 2][r >> 1], sel);
+        o.z = __builtin_amdgcn_perm(g[gq * 8 + 5][r >> 1], g[gq * 8 + 4][r >> 1], sel);
+        o.w = __builtin_amdgcn_perm(g[gq * 8 + 7][r >> 1], g[gq * 8 + 6][r >> 1], sel);
+        lds_write16_at<(gq * 128 + r) * kRowBytes>(st_addr + stage, o);
+      }
+    };
+#define PPMOE_BWD_IC(i) std::integral_constant<int, (i)>{}
+
+    // ---- prologue: tile 0 through set 0 into stage 0; tiles 1 and 2 in flight in sets 1 and 0 -----
+#pragma unroll
+    for (int i = 0; i < 16; ++i) gload(g0, 0, i);
+    gstore(g0, 0, PPMOE_BWD_IC(0)); gstore(g0, 0, PPMOE_BWD_IC(1)); gstore(g0, 0, PPMOE_BWD_IC(2)); gstore(g0, 0, PPMOE_BWD_IC(3));
+    gstore(g0, 0, PPMOE_BWD_IC(4)); gstore(g0, 0, PPMOE_BWD_IC(5)); gstore(g0, 0, PPMOE_BWD_IC(6)); gstore(g0, 0, PPMOE_BWD_IC(7));
+    gstore(g0, 0, PPMOE_BWD_IC(8)); gstore(g0, 0, PPMOE_BWD_IC(9)); gstore(g0, 0, PPMOE_BWD_IC(10)); gstore(g0, 0, PPMOE_BWD_IC(11));
+    gstore(g0, 0, PPMOE_BWD_IC(12)); gstore(g0, 0, PPMOE_BWD_IC(13)); gstore(g0, 0, PPMOE_BWD_IC(14)); gstore(g0, 0, PPMOE_BWD_IC(15));
+#pragma unroll
+    for (int i = 0; i < 16; ++i) gload(g1, 1, i);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) gload(g0, 2, i);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    u32x4 f0[8], f1[8];
+    const uint32_t fa0 = fa_addr, fb0 = fb_addr, fa1 = fa_addr + kStageBytes, fb1 = fb_addr + kStageBytes;
+    PPMOE_BWD_RA(f0, 0, 0, fa0); PPMOE_BWD_RB(f0, 0, 0, fb0); PPMOE_BWD_RB(f0, 1, 0, fb0); PPMOE_BWD_RA(f0, 1, 0, fa0);
+    PPMOE_BWD_RB(f0, 2, 0, fb0); PPMOE_BWD_RB(f0, 3, 0, fb0); PPMOE_BWD_RA(f0, 2, 0, fa0); PPMOE_BWD_RA(f0, 3, 0, fa0);
+
+    // One iteration: k-tile kt out of the stage at `fa_c / fb_c`, the staged tile kt + 1 (set G) into
+    // the stage at byte offset ST_N (fragment addresses fa_n / fb_n), then tile kt + 3 into set G.
+    // Waits: LDS operations issued after fragment read i of a k-step with writes: 15 - 2 i, without:
+    // 7 - i; issued in the current k-step before MFMA j: j with writes, (j + 1) / 2 without.
+#define PPMOE_BWD_ITER(kt, G, fa_c, fb_c, fa_n, fb_n, ST_N)                                                    \
+  do {                                                                                                         \
+    PPMOE_BWD_STEP(f0, f1, 1, fa_c, fb_c, PPMOE_BWD_WAIT6, PPMOE_BWD_WAIT6, PPMOE_BWD_WAIT6, PPMOE_BWD_WAIT7,  \
+                   PPMOE_BWD_WAIT7, PPMOE_BWD_WAIT9, PPMOE_BWD_WAIT10, PPMOE_BWD_ODD_W0);                      \
+    PPMOE_BWD_STEP(f1, f0, 2, fa_c, fb_c, PPMOE_BWD_WAIT13, PPMOE_BWD_WAIT12, PPMOE_BWD_WAIT11, PPMOE_BWD_WAIT11, \
+                   PPMOE_BWD_WAIT10, PPMOE_BWD_WAIT11, PPMOE_BWD_WAIT11, PPMOE_BWD_ODD_W1);                    \
+    PPMOE_BWD_STEP(f0, f1, 3, fa_c, fb_c, PPMOE_BWD_WAIT13, PPMOE_BWD_WAIT12, PPMOE_BWD_WAIT10, PPMOE_BWD_WAIT9, \
+                   PPMOE_BWD_WAIT8, PPMOE_BWD_WAIT7, PPMOE_BWD_WAIT6, PPMOE_BWD_ODD_G0);                       \
+    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_BWD_TIE8(f1) : : "memory");                                    \
+    __builtin_amdgcn_s_barrier();                                                                              \
+    asm volatile("" ::: "memory");                                                                             \
+    PPMOE_BWD_STEP(f1, f0, 0, fa_n, fb_n, PPMOE_BWD_NOWAIT, PPMOE_BWD_NOWAIT, PPMOE_BWD_NOWAIT, PPMOE_BWD_NOWAIT, \
+                   PPMOE_BWD_NOWAIT, PPMOE_BWD_NOWAIT, PPMOE_BWD_NOWAIT, PPMOE_BWD_ODD_G1);                    \
+  } while (0)
+
+    for (int kt = 0; kt < kt_count; kt += 2) {
+#define PPMOE_BWD_ODD_W0(i) gstore(g1, kStageBytes, PPMOE_BWD_IC(i))
+#define PPMOE_BWD_ODD_W1(i) gstore(g1, kStageBytes, PPMOE_BWD_IC(8 + (i)))
+#define PPMOE_BWD_ODD_G0(i) gload(g1, kt + 3, i)
+#define PPMOE_BWD_ODD_G1(i) gload(g1, kt + 3, 8 + (i))
+      PPMOE_BWD_ITER(kt, g1, fa0, fb0, fa1, fb1, kStageBytes);
+#undef PPMOE_BWD_ODD_W0
+#undef PPMOE_BWD_ODD_W1
+#undef PPMOE_BWD_ODD_G0
+#undef PPMOE_BWD_ODD_G1
+#define PPMOE_BWD_ODD_W0(i) gstore(g0, 0, PPMOE_BWD_IC(i))
+#define PPMOE_BWD_ODD_W1(i) gstore(g0, 0, PPMOE_BWD_IC(8 + (i)))
+#define PPMOE_BWD_ODD_G0(i) gload(g0, kt + 4, i)
+#define PPMOE_BWD_ODD_G1(i) gload(g0, kt + 4, 8 + (i))
+      PPMOE_BWD_ITER(kt + 1, g0, fa1, fb1, fa0, fb0, 0);
+#undef PPMOE_BWD_ODD_W0
+#undef PPMOE_BWD_ODD_W1
+#undef PPMOE_BWD_ODD_G0
+#undef PPMOE_BWD_ODD_G1
+    }
+    // (the fragments read behind the last barrier are not used; let them land before the registers die)
+    asm volatile("s_waitcnt lgkmcnt(0)" : PPMOE_BWD_TIE8(f0) : : "memory");
+  };
+  if (MODE == 0 && !stage_b) k_loop(std::true_type{});
+  else k_loop(std::false_type{});
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wm, wn, frow, half);
+}
+#undef PPMOE_BWD_ITER
+#undef PPMOE_BWD_IC
+#undef PPMOE_BWD_STEP
+#undef PPMOE_BWD_RA
+#undef PPMOE_BWD_RB
+#undef PPMOE_BWD_WAIT
+#undef PPMOE_BWD_MFMA
 
 // H = GeLU(U) and dU = dH * GeLU'(U) over the packed rows [0, offsets[n_exp]) x F, one row per block
 // iteration; dH and dU may be the same buffer.  tanh form:  s = 1 / (1 + exp(-2 z)),
@@ -340,35 +613,61 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   hipError_t e = launch_grouped_gemm(c.in_dtype, false, x_sliced, W1, U, offsets, N, rows, c.F, c.d, gemm_ws, s);
   if (e != hipSuccess) return e;
 
-  auto dgrad_grid = [&](int n_out) {
-    const int64_t m_tiles = (rows + BM - 1) / BM + N;   // upper bound on the sum of the ceilings
-    return static_cast<unsigned>((m_tiles * ((n_out + BN - 1) / BN) + 7) / 8 * 8);
-  };
-  auto wgrad_grid = [&](int m_out, int n_out) {
-    return static_cast<unsigned>((static_cast<int64_t>(N) * ((m_out + BM - 1) / BM) * ((n_out + BN - 1) / BN) + 7) / 8 * 8);
-  };
+  // Tile shape per launch: the pipelined 256 x 256 kernel (one block per CU, half the LDS and L2
+  // traffic per flop, latencies hidden by its schedule) unless that leaves more than half of the CUs
+  // without a tile; then 128 x 128 (two blocks per CU, compiler-scheduled; also K not a multiple of
+  // 64).  The host knows the row count only as a bound (the counts live on the device).
+  int n_cus = 256;
+  {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n_cus = prop.multiProcessorCount;
+  }
   static const hipError_t attrs = [] {
-    const void* kernels[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_BF16>),
-                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_BF16>),
-                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_F16>),
-                             reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_F16>)};
-    for (const void* k : kernels) {
-      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    const void* small[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_BF16, 128, 128>),
+                           reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_BF16, 128, 128>),
+                           reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_F16, 128, 128>),
+                           reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_F16, 128, 128>)};
+    const void* big[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_pipelined_kernel<0, MOE_BF16>),
+                         reinterpret_cast<const void*>(grouped_gemm_bwd_pipelined_kernel<1, MOE_BF16>),
+                         reinterpret_cast<const void*>(grouped_gemm_bwd_pipelined_kernel<0, MOE_F16>),
+                         reinterpret_cast<const void*>(grouped_gemm_bwd_pipelined_kernel<1, MOE_F16>)};
+    for (const void* k : small) {
+      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128, 128));
+      if (err != hipSuccess) return err;
+    }
+    for (const void* k : big) {
+      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(256, 256));
       if (err != hipSuccess) return err;
     }
     return hipSuccess;
   }();
   if (attrs != hipSuccess) return attrs;
-#define PPMOE_BWD(MODE, grid, a, b, cc, m, n, k)                                                               \
+  // MODE 0: m_out = the packed rows (their tiles per expert: at most rows / BM + N in all); MODE 1:
+  // m_out x n_out is one expert's weight matrix.
+  auto tiles_of = [&](int mode, int64_t m_out, int n_out, int bm, int bn) -> int64_t {
+    const int64_t nt = (n_out + bn - 1) / bn;
+    return mode == 0 ? ((m_out + bm - 1) / bm + N) * nt : static_cast<int64_t>(N) * ((m_out + bm - 1) / bm) * nt;
+  };
+#define PPMOE_BWD(MODE, a, b, cc, m, n, k, m_out)                                                              \
   do {                                                                                                         \
-    if (c.in_dtype == MOE_F16)                                                                                 \
-      grouped_gemm_bwd_kernel<MODE, MOE_F16><<<grid, kThreads, kLdsBytes, s>>>(a, b, cc, offsets, N, m, n, k);  \
+    const bool big = 2 * tiles_of(MODE, m_out, n, 256, 256) >= n_cus && (MODE == 1 || (k) % BK == 0);          \
+    const int t = big ? 256 : 128;                                                                             \
+    const unsigned grid = static_cast<unsigned>((tiles_of(MODE, m_out, n, t, t) + 7) / 8 * 8);                 \
+    const size_t shm = lds_bytes(t, t);                                                                        \
+    if (big && c.in_dtype == MOE_F16)                                                                          \
+      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_F16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);       \
+    else if (big)                                                                                              \
+      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_BF16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);      \
+    else if (c.in_dtype == MOE_F16)                                                                            \
+      grouped_gemm_bwd_kernel<MODE, MOE_F16, 128, 128><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);       \
     else                                                                                                       \
-      grouped_gemm_bwd_kernel<MODE, MOE_BF16><<<grid, kThreads, kLdsBytes, s>>>(a, b, cc, offsets, N, m, n, k); \
+      grouped_gemm_bwd_kernel<MODE, MOE_BF16, 128, 128><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);      \
   } while (0)
 
   // dH = dY B^T  (into the dU buffer), then H = GeLU(U), dU = dH * GeLU'(U) in place
-  PPMOE_BWD(0, dgrad_grid(c.F), dy, w2, dU, 0, c.F, c.d);
+  PPMOE_BWD(0, dy, w2, dU, 0, c.F, c.d, rows);
   {
     const int blocks = static_cast<int>(rows < 256 * 16 ? (rows > 0 ? rows : 1) : 256 * 16);
     if (c.in_dtype == MOE_F16)
@@ -377,10 +676,10 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
       act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
   }
   // dX = dU A^T
-  PPMOE_BWD(0, dgrad_grid(c.d), dU, w1, dX, 0, c.d, c.F);
+  PPMOE_BWD(0, dU, w1, dX, 0, c.d, c.F, rows);
   // dB^T[i] = dY_i^T H_i  ([d, F]);  dA^T[i] = dU_i^T X_i  ([F, d])
-  PPMOE_BWD(1, wgrad_grid(c.d, c.F), dy, H, dW2, c.d, c.F, 0);
-  PPMOE_BWD(1, wgrad_grid(c.F, c.d), dU, xs, dW1, c.F, c.d, 0);
+  PPMOE_BWD(1, dy, H, dW2, c.d, c.F, 0, c.d);
+  PPMOE_BWD(1, dU, xs, dW1, c.F, c.d, 0, c.F);
 #undef PPMOE_BWD
   return hipGetLastError();
 }
