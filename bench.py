@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "grouped_gemm_gpt_top1_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "grouped_gemm_{workload}_hbm_traffic.txt")
 
 
 def measured_traffic(workload, stage):
@@ -35,7 +35,7 @@ def measured_traffic(workload, stage):
     rocprofv3 --pmc summary (the counters cannot be read from inside this process).  None when
     there is no summary for this workload."""
     try:
-        text = open(TRAFFIC_FILE).read()
+        text = open(TRAFFIC_FILE.format(workload=workload)).read()
     except OSError:
         return None
     if f"workload: {workload}" not in text:
