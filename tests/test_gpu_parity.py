@@ -294,6 +294,10 @@ def test_handover_that_never_arrives_is_recomputed(d, F, counts):
     ("bf16", 512, 1024, [1024, 1000, 0, 24]),
     ("bf16", 1024, 256, [129, 128, 600, 3]),
     ("f16", 256, 512, [300, 0, 130, 1]),
+    # large enough for the 256 x 256 pipelined backward kernel in all four products: odd numbers of
+    # k-tiles (17 and 33), partial column tiles, experts of 0, 1 and 65 rows, ragged contraction lengths
+    ("bf16", 1088, 2112, [700, 0, 1, 2500, 65, 2800]),
+    ("f16", 576, 4160, [300, 1500, 31, 0, 2000]),
 ])
 def test_expert_ffn_backward_on_oracle_rows(dtype, d, F, counts):
     """moe_expert_ffn_backward against the oracle's chain rule on ragged groups (empty experts, one-row
