@@ -9,9 +9,11 @@
 //   dH[r, f] = sum_c dY[r, c] W2[i][c, f],        dX[r, c] = sum_f dU[r, f] W1[i][f, c],
 // and the two weight gradients contract over the packed rows of the expert
 //   dW2[i][c, f] = sum_r dY[r, c] H[r, f],        dW1[i][f, c] = sum_r dU[r, f] X[r, c],
-// so in both an operand reaches the matrix cores across its rows.  One kernel covers the two forms:
-// block tile 256 x 256, 256 x 128 or 128 x 128 (x 64 along k), four wavefronts (2 x 2), each a quarter
-// of the tile as MFMA 32x32x16 blocks; operand
+// so in both an operand reaches the matrix cores across its rows.  Two kernels cover the two forms
+// (MODE 0: data gradient, MODE 1: weight gradient): a hand-scheduled one with 256 x 256 x 64 block
+// tiles for launches with enough tiles to fill the chip, and a plain one with 128 x 128 x 64 tiles
+// (two blocks per CU, scheduled by the compiler) for everything else.  Both: four wavefronts (2 x 2),
+// each a quarter of the tile as MFMA 32x32x16 blocks; operand
 // tiles go through LDS as [row][k] with k contiguous (rows 144 bytes apart, 16-byte chunks
 // XOR-swizzled: fragment reads and staging writes are free of bank conflicts); an operand whose k
 // runs along memory rows is transposed in registers on its way into LDS (a thread loads an 8 x 8
