@@ -77,6 +77,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--settle", type=int, default=80,
+                    help="layer calls made before the warm-up steps so that the device's power management has "
+                         "settled (from idle it boosts, over-corrects for about 10 ms and takes about 25 ms "
+                         "of load to reach the clock it then keeps): the timed steps measure steady state")
     ap.add_argument("--config", type=int, default=1, help="index into synth.CONFIGS (1 = headline)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,6 +124,8 @@ def main():
         B.moe_layer_forward(cfg, dev["x"], dev["Wg_t"], bias, dev["W1_t"], dev["W2_t"], out, ws,
                             stage_events=events)
 
+    for _ in range(max(0, args.settle)):
+        step()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -156,7 +162,7 @@ def main():
             with torch.cuda.graph(graph, stream=side):
                 step()
         torch.cuda.current_stream().wait_stream(side)
-        for _ in range(args.warmup):
+        for _ in range(max(0, args.settle) + args.warmup):   # (the capture left the device idle: settle again)
             graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -172,6 +178,8 @@ def main():
     # Timed region 2: the same K steps with HIP events recorded on the stream around every stage
     # (each record costs a few microseconds, which is why region 1 carries the headline number).
     events = [[B.moe_event_create() for _ in range(B.MOE_NUM_STAGES + 1)] for _ in range(K)]
+    for _ in range(max(0, args.settle)):
+        step()
     torch.cuda.synchronize()
     for i in range(K):
         step(events[i])
