@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void dx_kernel(const bf16_t* __restrict__
 // dWg: the tokens are cut into kChunks chunks; block (column block, chunk) adds up its chunk for its
 // 2048 columns (8 per thread), eight experts at a time, and stores a partial sum; a second launch
 // adds the chunks in order.
-constexpr int kChunks = 64;
+constexpr int kChunks = 256;
 constexpr int kEG = 8;
 template <int DT>
 __global__ __launch_bounds__(kThreads) void dwg_partial_kernel(const bf16_t* __restrict__ x,
@@ -174,22 +174,33 @@ __global__ __launch_bounds__(kThreads) void dwg_partial_kernel(const bf16_t* __r
 #pragma unroll
       for (int q = 0; q < 8; ++q) acc[g][q] = 0.f;
     float bsum = 0.f;   // (thread g of column block 0 also adds up dlogits[:, e0 + g])
-    for (int t = tb; t < te; ++t) {
-      float dl[kEG];
+    // four tokens at a time: their loads go out together, the sums keep the token order
+    for (int t0 = tb; t0 < te; t0 += 4) {
+      float dl[4][kEG];
+      u32x4 xr[4];
 #pragma unroll
-      for (int g = 0; g < kEG; ++g) dl[g] = e0 + g < E ? dlogits[static_cast<int64_t>(t) * E + e0 + g] : 0.f;
-      if (blockIdx.x == 0 && threadIdx.x < kEG) {
+      for (int j = 0; j < 4; ++j) {
+        const int t = min(t0 + j, te - 1);
+        xr[j] = (c < d && t0 + j < te) ? *reinterpret_cast<const u32x4*>(x + static_cast<int64_t>(t) * d + c) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int g = 0; g < kEG; ++g)
-          if (static_cast<int>(threadIdx.x) == g) bsum += dl[g];
+          dl[j][g] = (t0 + j < te && e0 + g < E) ? dlogits[static_cast<int64_t>(t) * E + e0 + g] : 0.f;
       }
-      if (c < d) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (blockIdx.x == 0 && threadIdx.x < kEG) {
+#pragma unroll
+          for (int g = 0; g < kEG; ++g)
+            if (static_cast<int>(threadIdx.x) == g) bsum += dl[j][g];
+        }
         float f[8];
-        widen8<DT>(x + static_cast<int64_t>(t) * d + c, f);
+        const uint32_t w4[4] = {xr[j].x, xr[j].y, xr[j].z, xr[j].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) Elem16<DT>::widen2(w4[q], f[2 * q], f[2 * q + 1]);
 #pragma unroll
         for (int g = 0; g < kEG; ++g)
 #pragma unroll
-          for (int q = 0; q < 8; ++q) acc[g][q] = fmaf(dl[g], f[q], acc[g][q]);
+          for (int q = 0; q < 8; ++q) acc[g][q] = fmaf(dl[j][g], f[q], acc[g][q]);
       }
     }
     if (c < d) {
