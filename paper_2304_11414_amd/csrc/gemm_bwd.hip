@@ -165,9 +165,12 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
     const int m_tiles = (M + BM - 1) / BM;
     int tile = xcd_tile(blockIdx.x, n_exp * m_tiles * n_tiles);
     if (tile < 0) return false;
-    ti.expert = tile / (m_tiles * n_tiles);
-    tile -= ti.expert * m_tiles * n_tiles;
-    const int mt = tile / n_tiles, nt = tile - mt * n_tiles;
+    // Tiles ordered row tile, then expert, then column tile: each XCD's run of the list goes through
+    // all the experts, so an expert with many rows (a long contraction) is not one XCD's alone.
+    const int mt = tile / (n_exp * n_tiles);
+    tile -= mt * n_exp * n_tiles;
+    ti.expert = tile / n_tiles;
+    const int nt = tile - ti.expert * n_tiles;
     ti.m0 = mt * BM;
     ti.col0 = nt * BN;
     const int lo = offsets[ti.expert], hi = offsets[ti.expert + 1];
