@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ppmoe.h"
 
 namespace ppmoe {
@@ -126,6 +128,22 @@ hipError_t launch_permute(const moe_config& c, int64_t cap, const int32_t* exper
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                           int32_t* seg_scratch, hipStream_t s, int seg_assign = kSegment,
                           bool counted = false, const AuxOut* aux = nullptr);
+
+// Runs `set_up` (returning hipError_t) the first time it is reached with a given device current and
+// remembers, per device, that it has run: kernel attributes such as the dynamic-LDS limit belong to
+// the device they were set on.  `done`: one bit per device ordinal (devices beyond 63 run it every
+// time; the attributes are idempotent, as is a race between two first calls).
+template <typename F>
+inline hipError_t once_per_device(std::atomic<uint64_t>& done, F set_up) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t(1) << dev : 0;
+  if (bit != 0 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = set_up();
+  if (e == hipSuccess && bit != 0) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // Allocation-free dispatch: device address of this device's file-scope scratch array of
 // kStaticScratchBytes bytes (looked up on the first call per device, with that device current).

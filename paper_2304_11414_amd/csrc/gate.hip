@@ -461,16 +461,17 @@ static hipError_t launch_bf16(const moe_config& c, const void* x, const void* Wg
   constexpr int kTok = 16 * MT;
   constexpr size_t lds = kTok * (2048 / MT * 2 + 16) + kTok * (NT * 16 + 1) * sizeof(float) +
                          kTok * kMaxTopK * sizeof(int32_t);
-  static bool attr_set = false;   // (an idempotent attribute: a race between two first calls is harmless)
-  if (!attr_set) {
+  static std::atomic<uint64_t> attr_set{0};
+  const hipError_t attr = once_per_device(attr_set, [] {
     const void* kernels[] = {reinterpret_cast<const void*>(gate_rows_kernel<NT, MT, MOE_BF16>),
                              reinterpret_cast<const void*>(gate_rows_kernel<NT, MT, MOE_F16>)};
     for (const void* kern : kernels) {
       hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
     }
-    attr_set = true;
-  }
+    return hipSuccess;
+  });
+  if (attr != hipSuccess) return attr;
   const int n_groups = (c.T + kTok - 1) / kTok;
   const int blocks = n_groups < 512 ? n_groups : 512;   // two resident blocks per compute unit walk over the groups
 #define PPMOE_GATE(DT)                                                                                 \

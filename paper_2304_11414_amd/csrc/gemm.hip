@@ -291,7 +291,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 // ---------------------------------------------------------------------------------------------
 
 static hipError_t ensure_lds_attr() {
-  static hipError_t done = [] {
+  static std::atomic<uint64_t> done{0};
+  return once_per_device(done, [] {
     const void* kernels[] = {reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<true, MOE_BF16>),
                              reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<false, MOE_BF16>),
                              reinterpret_cast<const void*>(grouped_gemm_bf16_kernel<true, MOE_F16>),
@@ -301,8 +302,7 @@ static hipError_t ensure_lds_attr() {
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
-  }();
-  return done;
+  });
 }
 
 hipError_t launch_grouped_gemm(int in_dtype, bool gelu, const void* A, const void* B, void* C,

@@ -629,7 +629,8 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
       n_cus = prop.multiProcessorCount;
   }
-  static const hipError_t attrs = [] {
+  static std::atomic<uint64_t> attrs_done{0};
+  const hipError_t attrs = once_per_device(attrs_done, [] {
     const void* small[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_BF16, 128, 128>),
                            reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<1, MOE_BF16, 128, 128>),
                            reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_F16, 128, 128>),
@@ -647,7 +648,7 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
       if (err != hipSuccess) return err;
     }
     return hipSuccess;
-  }();
+  });
   if (attrs != hipSuccess) return attrs;
   // MODE 0: m_out = the packed rows (their tiles per expert: at most rows / BM + N in all); MODE 1:
   // m_out x n_out is one expert's weight matrix.
