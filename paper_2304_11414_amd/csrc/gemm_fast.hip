@@ -269,16 +269,13 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   //    starting at (8 j + x) cus of the tile list, one per CU.  The list is ordered so that those
   //    cus tiles are a block of a few row tiles x a few column tiles (see big_tile_at): they run at
   //    the same time and in step along K, which is what lets the L2 serve a panel once for several
-  //    CUs.  What is left after the whole rounds (fewer than 8 cus tiles) is split evenly: one more,
-  //    partial round per XCD.
-  //  * The small tiles (an eighth per XCD) -- and the big ones too when there is no whole round and
-  //    an XCD has fewer than `cus` of them (few rows per expert, or a narrow output) -- form one
-  //    stream of k-tiles that is cut into shares, so that a 3-row tail of an expert does not cost a
-  //    CU a whole tile slot and every CU has work.  A tile cut this way is finished by the CU that
-  //    holds its first k-tile.
-  // (Cutting the left-over big tiles of a last, partial round the same way was measured slower than
-  // running that round: the CUs fall out of step along K, the L2 hit rate drops, and handing over
-  // 256 KiB of partial sums costs about a tenth of a short tile per cut.)
+  //    CUs.  What is left after the whole rounds (fewer than 8 cus tiles) is split evenly over the
+  //    XCDs: one more, partial round per XCD -- unless an XCD's part is at most a quarter of its
+  //    CUs, see below.
+  //  * The small tiles (an eighth per XCD), and before them those few left-over big tiles, form one
+  //    stream of k-tiles that is cut into shares, so that a 3-row tail of an expert, or one tile more
+  //    than the chip has CUs, does not cost a whole tile slot and every CU has work.  A tile cut
+  //    this way is finished by the CU that holds its first k-tile.
   const int n_tiles = (Nout + BN - 1) / BN;
   const int KT = K / BK;
   int total_big, total_small;
@@ -294,8 +291,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   const int lx1 = full_rounds * chip + static_cast<int>(static_cast<int64_t>(rem) * (xcd + 1) / 8);
   const int sx0 = static_cast<int>(static_cast<int64_t>(total_small) * xcd / 8);
   const int sx1 = static_cast<int>(static_cast<int64_t>(total_small) * (xcd + 1) / 8);
-  const bool cut_big = full_rounds == 0 && lx1 - lx0 < cus;
-  const int rounds = cut_big ? 0 : full_rounds + (lx1 > lx0 ? 1 : 0);
+  // The XCD's part of the remainder: a few tiles (up to a quarter of its CUs) are cut as part of the
+  // stream, so that they do not cost a round of their own in which most CUs idle; more of them run as
+  // one more, partial round (cutting them was measured slower: the hand-over of a big tile's 256 KiB
+  // of partial sums and the CUs falling out of step along K cost more than the idle CUs).
+  const bool cut_big = lx1 > lx0 && (lx1 - lx0) * 4 <= cus;
+  const int rounds = full_rounds + (!cut_big && lx1 > lx0 ? 1 : 0);
   const int stream_big = cut_big ? lx1 - lx0 : 0;                  // big tiles at the head of the stream
   const int64_t units = static_cast<int64_t>(stream_big + sx1 - sx0) * KT;
   // Shares shorter than kMinShare k-tiles are not worth their hand-over: fewer CUs then take part.

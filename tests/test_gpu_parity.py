@@ -208,6 +208,9 @@ def ragged_offsets(counts):
     ("bf16", 256, 4096, [129, 128, 600]),         # long K in the second GEMM
     ("bf16", 8192, 256, [33, 64, 65, 32]),        # only small tiles, each cut between eight CUs
     ("bf16", 2048, 512, [32, 33, 64, 65, 128, 129, 0, 1]),   # every small-tile height boundary
+    # 33 row tiles x 8 column tiles: one round of the whole chip and one big tile left per XCD, which is
+    # cut into the stream (hand-over of a big tile's partial sums after whole rounds)
+    ("bf16", 2048, 2048, [2304, 2048, 2048, 2048]),
     ("f32", 64, 136, [70, 0, 64, 1]),
     ("f32", 256, 1024, [64, 64, 64, 64]),
     ("f16", 192, 520, [300, 0, 513, 1, 255, 256]),          # general 16-bit kernel (K not a multiple of 64)
@@ -236,6 +239,7 @@ CUT_TILE_CASES = [
     (256, 4096, [129, 128, 600]),         # long K in the second GEMM
     (8192, 256, [33, 64, 65, 32]),        # only small tiles, each cut between eight CUs
     (512, 1024, [1024, 1000, 0, 24]),
+    (2048, 2048, [2304, 2048, 2048, 2048]),   # a round of the whole chip, then one cut big tile per XCD
 ]
 
 
