@@ -291,11 +291,18 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bf16_fast_kernel(
   const int lx1 = full_rounds * chip + static_cast<int>(static_cast<int64_t>(rem) * (xcd + 1) / 8);
   const int sx0 = static_cast<int>(static_cast<int64_t>(total_small) * xcd / 8);
   const int sx1 = static_cast<int>(static_cast<int64_t>(total_small) * (xcd + 1) / 8);
-  // The XCD's part of the remainder: a few tiles (up to a quarter of its CUs) are cut as part of the
-  // stream, so that they do not cost a round of their own in which most CUs idle; more of them run as
-  // one more, partial round (cutting them was measured slower: the hand-over of a big tile's 256 KiB
-  // of partial sums and the CUs falling out of step along K cost more than the idle CUs).
-  const bool cut_big = lx1 > lx0 && (lx1 - lx0) * 4 <= cus;
+  // The XCD's part of the remainder (r tiles) either runs as one more, partial round, in which
+  // cus - r CUs idle for a tile's KT k-tiles, or joins the stream and is cut among all CUs, which
+  // costs the hand-over of the big tiles' partial sums (256 KiB each, and an epilogue that waits for
+  // them: about 25 k-tiles' time) and, where tiles share panels, the L2's help: the CUs of a stream
+  // are not in step along K.  It is cut when it is small (up to a quarter of the CUs: one tile more
+  // than the chip has CUs must not cost a round); and, when there is no whole round at all (few tiles
+  // per expert: the tiles share little), when the idle time of the partial round would be larger
+  // than that price (long contractions).  Measured: with whole rounds before it, cutting 12 tiles of
+  // 320 k-tiles per XCD costs 6 % of the launch, running them as a round 3 %.
+  const int rem_x = lx1 - lx0;
+  const bool cut_big = rem_x > 0 && (rem_x * 4 <= cus ||
+                                     (full_rounds == 0 && static_cast<int64_t>(KT) * (cus - rem_x) >= 25 * cus));
   const int rounds = full_rounds + (!cut_big && lx1 > lx0 ? 1 : 0);
   const int stream_big = cut_big ? lx1 - lx0 : 0;                  // big tiles at the head of the stream
   const int64_t units = static_cast<int64_t>(stream_big + sx1 - sx0) * KT;
