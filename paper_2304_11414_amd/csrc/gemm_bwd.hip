@@ -19,7 +19,9 @@
 // runs along memory rows is transposed in registers on its way into LDS (a thread loads an 8 x 8
 // block as eight 16-byte pieces, one per memory row, and writes eight 16-byte chunks, one per tile
 // row).  Weight gradients are float32 (the precision gradients are accumulated in); data gradients
-// have the layer's 16-bit type.  Sums have a fixed order: bitwise reproducible.
+// have the layer's 16-bit type.  Sums have a fixed order: bitwise reproducible.  Where the data
+// gradient's contraction is long, the experts' last few rows may leave the 256 x 256 launch for a
+// split-contraction launch of their own (tails_split_off below).
 
 #include <type_traits>
 
@@ -120,10 +122,37 @@ struct TileInfo {
   Operand opA, opB;   // opA: the operand whose tile rows are the output rows; opB: the output columns
 };
 
+// Data gradient with a long contraction: an expert's last rows, when they are at most kTailRows past a
+// multiple of 256, cost the 256 x 256 kernel a whole tile each, and with few tiles per CU a whole
+// extra round of the chip.  They can go to a second launch instead (128-row tiles, the contraction
+// split over several blocks, partial sums added up in a fixed order by a third launch).  Every block
+// of the three launches takes that decision from the row counts alone, so they all agree:
+// tails are split off when that saves the 256 x 256 launch a round and the tail tiles are cheap enough.
+constexpr int kTailRows = 128;
+constexpr int kTailSplitsMax = 8;
+__device__ __forceinline__ int tail_rows_of(int n) {
+  const int t = n & 255;
+  return (t > 0 && t <= kTailRows) ? t : 0;
+}
+__device__ __forceinline__ bool tails_split_off(const int32_t* __restrict__ offsets, int n_exp, int N, int tail_cus) {
+  if (tail_cus <= 0) return false;   // (the launcher has not provided for the two extra launches)
+  const int n_tiles = (N + 255) / 256;
+  int all = 0, big = 0, tails = 0;
+  for (int i = 0; i < n_exp; ++i) {
+    const int n = offsets[i + 1] - offsets[i], t = tail_rows_of(n);
+    all += (n + 255) / 256 * n_tiles;
+    big += (n - t + 255) / 256 * n_tiles;
+    tails += t > 0;
+  }
+  const int rounds_all = (all + tail_cus - 1) / tail_cus, rounds_big = (big + tail_cus - 1) / tail_cus;
+  return rounds_big < rounds_all && tails * N <= 24576;
+}
+
+// tail_cus (MODE 0 only): 0, or the number of CUs when the launcher runs the tail launches as well.
 template <int MODE, int BM, int BN>
 __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                             const int32_t* __restrict__ offsets, int n_exp, int M, int N,
-                                            int K, TileInfo& ti) {
+                                            int K, TileInfo& ti, int tail_cus = 0) {
   const int n_tiles = (N + BN - 1) / BN;
   ti.expert = ti.row0 = ti.rows = ti.col0 = ti.m0 = ti.kt_count = 0;
   // Consecutive block ids land on different XCDs (round robin over 8): remap so that each XCD works on
@@ -135,14 +164,19 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
   };
   if (MODE == 0) {
     // tiles ordered expert-major, then n-tile, then m-tile; blocks past the last tile leave
+    const bool no_tails = tails_split_off(offsets, n_exp, N, tail_cus);
     int total = 0;
-    for (int i = 0; i < n_exp; ++i) total += (offsets[i + 1] - offsets[i] + BM - 1) / BM * n_tiles;
+    for (int i = 0; i < n_exp; ++i) {
+      const int n = offsets[i + 1] - offsets[i];
+      total += (n - (no_tails ? tail_rows_of(n) : 0) + BM - 1) / BM * n_tiles;
+    }
     int tile = xcd_tile(blockIdx.x, total);
     if (tile < 0) return false;
     bool found = false;
     int lo = offsets[0];
     for (int i = 0; i < n_exp && !found; ++i) {
-      const int hi = offsets[i + 1];
+      const int next = offsets[i + 1];
+      const int hi = next - (no_tails ? tail_rows_of(next - lo) : 0);
       const int m_tiles = (hi - lo + BM - 1) / BM;
       const int here = m_tiles * n_tiles;
       if (tile < here) {
@@ -154,7 +188,7 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
         found = true;
       } else {
         tile -= here;
-        lo = hi;
+        lo = next;
       }
     }
     if (!found) return false;
@@ -165,12 +199,19 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
     const int m_tiles = (M + BM - 1) / BM;
     int tile = xcd_tile(blockIdx.x, n_exp * m_tiles * n_tiles);
     if (tile < 0) return false;
-    // Tiles ordered row tile, then expert, then column tile: each XCD's run of the list goes through
-    // all the experts, so an expert with many rows (a long contraction) is not one XCD's alone.
-    const int mt = tile / (n_exp * n_tiles);
-    tile -= mt * n_exp * n_tiles;
-    ti.expert = tile / n_tiles;
-    const int nt = tile - ti.expert * n_tiles;
+    // Tiles ordered in blocks of up to 32 (ba row tiles x bb column tiles of one expert: what the 32
+    // CUs of an XCD hold at a time, sharing ba + bb operand panels), the blocks of a position going
+    // through all the experts before the next position: each XCD's run of the list visits every
+    // expert, so an expert with many rows (a long contraction) is not one XCD's alone.
+    int bb = n_tiles % 8 == 0 ? 8 : n_tiles % 4 == 0 ? 4 : n_tiles % 2 == 0 ? 2 : 1;
+    int ba = 32 / bb;
+    while (ba > 1 && m_tiles % ba != 0) ba >>= 1;
+    const int per_block = ba * bb, blocks_n = n_tiles / bb;
+    const int blk = tile / (n_exp * per_block);
+    tile -= blk * n_exp * per_block;
+    ti.expert = tile / per_block;
+    const int w = tile - ti.expert * per_block;
+    const int mt = (blk / blocks_n) * ba + w / bb, nt = (blk % blocks_n) * bb + w % bb;
     ti.m0 = mt * BM;
     ti.col0 = nt * BN;
     const int lo = offsets[ti.expert], hi = offsets[ti.expert + 1];
@@ -218,21 +259,14 @@ __device__ __forceinline__ void store_tile_output(const f32x16 (&acc)[BM / 64][B
   }
 }
 
-// MODE 0 (data gradient):   C[r, n]    = sum_k A[r, k] * B[i][k, n]   for the rows r of expert i
-//                           A [rows, K] 16-bit, B [n_exp, K, N] 16-bit, C [rows, N] 16-bit
-// MODE 1 (weight gradient): C[i][m, n] = sum_{r in expert i} A[r, m] * B[r, n]
-//                           A [rows, M] 16-bit, B [rows, N] 16-bit, C [n_exp, M, N] float32
-template <int MODE, int DT, int BM, int BN>
-__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
-    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+// One output tile's products over the k-tiles [kt_begin, kt_end) into `acc`: two LDS stages, the next
+// k-tile's loads in flight while the current one is multiplied.  SKIP_DEAD: 32-row blocks past the
+// tile's last valid row are not multiplied (their accumulators stay zero).
+template <int MODE, int DT, int BM, int BN, bool SKIP_DEAD>
+__device__ __forceinline__ void accumulate_tile(const TileInfo& ti, int kt_begin, int kt_end,
+                                                f32x16 (&acc)[BM / 64][BN / 64], unsigned char* lds) {
   typedef typename Elem16<DT>::vec8 vec8;
-
-  TileInfo ti;
-  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti)) return;
   const Operand opA = ti.opA, opB = ti.opB;
-  const int kt_count = ti.kt_count;
   constexpr bool kAContig = MODE == 0;   // A[r, k]: k contiguous only for the data gradient
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -242,12 +276,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   // staging: wavefronts 0, 1 bring in the A tile, 2, 3 the B tile
   const bool stage_b = wave >= 2;
   const int stage_half = wave & 1;
+  const int live_rows = ti.rows - wm * (BM / 2);   // valid rows of this wavefront's half of the tile
 
   constexpr int MI = BM / 64, NI = BN / 64;      // 32 x 32 blocks per wavefront, along m and along n
   constexpr int kATileBytes = BM * kRowBytes;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int SR = BM > BN ? BM : BN;          // (the staging registers fit the larger operand tile)
-  f32x16 acc[MI][NI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -264,15 +298,15 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
     if (stage_b) store_tile<false, BN>(buf + kATileBytes, stage_half, lane, g);
     else store_tile<kAContig, BM>(buf, stage_half, lane, g);
   };
-  if (kt_count > 0) {
-    load(0);
+  if (kt_end > kt_begin) {
+    load(kt_begin);
     store(lds);
   }
   __syncthreads();
-  for (int kt = 0; kt < kt_count; ++kt) {
-    unsigned char* cur = lds + (kt & 1) * kStageBytes;
-    unsigned char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-    if (kt + 1 < kt_count) load(kt + 1);
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    unsigned char* cur = lds + ((kt - kt_begin) & 1) * kStageBytes;
+    unsigned char* nxt = lds + ((kt - kt_begin + 1) & 1) * kStageBytes;
+    if (kt + 1 < kt_end) load(kt + 1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       vec8 fa[MI], fb[NI];
@@ -283,16 +317,115 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
       for (int ni = 0; ni < NI; ++ni)
         fb[ni] = *reinterpret_cast<const vec8*>(cur + kATileBytes + lds_chunk(wn * (BN / 2) + ni * 32 + frow, ks * 2 + half));
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
+      for (int mi = 0; mi < MI; ++mi) {
+        if (SKIP_DEAD && mi * 32 >= live_rows) continue;   // (uniform over the wavefront)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = Elem16<DT>::mfma32(fb[ni], fa[mi], acc[mi][ni]);   // D[n][m]: lane = row m, registers = columns n
+      }
     }
-    if (kt + 1 < kt_count) store(nxt);
+    if (kt + 1 < kt_end) store(nxt);
     __syncthreads();
   }
+}
 
-  store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wm, wn, frow, half);
+// MODE 0 (data gradient):   C[r, n]    = sum_k A[r, k] * B[i][k, n]   for the rows r of expert i
+//                           A [rows, K] 16-bit, B [n_exp, K, N] 16-bit, C [rows, N] 16-bit
+// MODE 1 (weight gradient): C[i][m, n] = sum_{r in expert i} A[r, m] * B[r, n]
+//                           A [rows, M] 16-bit, B [rows, N] 16-bit, C [n_exp, M, N] float32
+template <int MODE, int DT, int BM, int BN>
+__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
+    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  TileInfo ti;
+  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti)) return;
+  f32x16 acc[BM / 64][BN / 64];
+  accumulate_tile<MODE, DT, BM, BN, false>(ti, 0, ti.kt_count, acc, lds);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wave >> 1, wave & 1, lane & 31, lane >> 5);
+}
+
+// The split-off tails of the data gradient (see tails_split_off): block (expert, column tile, split)
+// multiplies the expert's tail rows (at most kTailRows) by a 128-column panel over its share of the
+// contraction and leaves float32 partial sums in `partial` [splits][n_exp][kTailRows][N].
+template <int DT>
+__global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_tail_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, float* __restrict__ partial,
+    const int32_t* __restrict__ offsets, int n_exp, int N, int K, int splits, int tail_cus) {
+  constexpr int BM = kTailRows, BN = 128;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  if (!tails_split_off(offsets, n_exp, N, tail_cus)) return;
+  const int n_tiles = (N + BN - 1) / BN;
+  int b = blockIdx.x;
+  const int nt = b % n_tiles;
+  b /= n_tiles;
+  const int split = b % splits, expert = b / splits;
+  const int lo = offsets[expert], hi = offsets[expert + 1];
+  const int tail = tail_rows_of(hi - lo);
+  if (tail == 0) return;
+  TileInfo ti;
+  ti.expert = expert;
+  ti.row0 = hi - tail;
+  ti.rows = tail;
+  ti.col0 = nt * BN;
+  ti.m0 = 0;
+  ti.kt_count = (K + BK - 1) / BK;
+  ti.opA = Operand{A + static_cast<int64_t>(ti.row0) * K, K, tail, K};
+  ti.opB = Operand{B + static_cast<int64_t>(expert) * K * N + ti.col0, N, min(BN, N - ti.col0), K};
+  const int per = (ti.kt_count + splits - 1) / splits;
+  const int kt_begin = split * per, kt_end = min(ti.kt_count, kt_begin + per);
+  f32x16 acc[BM / 64][BN / 64];
+  accumulate_tile<0, DT, BM, BN, true>(ti, kt_begin, kt_end, acc, lds);
+
+  // lane: row frow of each 32-row block; register v: column (v / 4) * 8 + half * 4 + v % 4
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1, frow = lane & 31, half = lane >> 5;
+  float* out = partial + (static_cast<int64_t>(split) * n_exp + expert) * kTailRows * N;
+  const int cols = min(BN, N - ti.col0);
+#pragma unroll
+  for (int mi = 0; mi < BM / 64; ++mi) {
+    const int m = wm * (BM / 2) + mi * 32 + frow;
+    if (m >= tail) continue;
+#pragma unroll
+    for (int ni = 0; ni < BN / 64; ++ni)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn * (BN / 2) + ni * 32 + q * 8 + half * 4;
+        if (n < cols)
+          *reinterpret_cast<float4*>(out + static_cast<int64_t>(m) * N + ti.col0 + n) =
+              make_float4(acc[mi][ni][q * 4 + 0], acc[mi][ni][q * 4 + 1], acc[mi][ni][q * 4 + 2], acc[mi][ni][q * 4 + 3]);
+      }
+  }
+}
+
+// Adds the tail kernel's partial sums in split order and stores the tail rows of C [rows, N] (16-bit).
+// One block per (expert, tail row), a thread per 8 columns.
+template <int DT>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
+                                                          const int32_t* __restrict__ offsets, int n_exp, int N,
+                                                          int splits, int tail_cus) {
+  if (!tails_split_off(offsets, n_exp, N, tail_cus)) return;
+  const int expert = blockIdx.x / kTailRows, r = blockIdx.x % kTailRows;
+  const int lo = offsets[expert], hi = offsets[expert + 1];
+  const int tail = tail_rows_of(hi - lo);
+  if (r >= tail) return;
+  bf16_t* crow = C + static_cast<int64_t>(hi - tail + r) * N;
+  for (int n = threadIdx.x * 8; n < N; n += 256 * 8) {   // (N is a multiple of 8)
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < splits; ++sp) {
+      const float* p = partial + ((static_cast<int64_t>(sp) * n_exp + expert) * kTailRows + r) * N + n;
+      const float4 u = *reinterpret_cast<const float4*>(p), w = *reinterpret_cast<const float4*>(p + 4);
+      a[0] += u.x; a[1] += u.y; a[2] += u.z; a[3] += u.w;
+      a[4] += w.x; a[5] += w.y; a[6] += w.z; a[7] += w.w;
+    }
+    u32x4 o;
+    o.x = Elem16<DT>::pack2(a[0], a[1]);
+    o.y = Elem16<DT>::pack2(a[2], a[3]);
+    o.z = Elem16<DT>::pack2(a[4], a[5]);
+    o.w = Elem16<DT>::pack2(a[6], a[7]);
+    *reinterpret_cast<u32x4*>(crow + n) = o;
+  }
 }
 
 // The same products on a 256 x 256 x 64 tile with one wavefront per SIMD (256 accumulator registers),
@@ -324,7 +457,7 @@ __device__ __forceinline__ void lds_write16_at(uint32_t addr, const u32x4& v) {
 template <int MODE, int DT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_pipelined_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ C,
-    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K) {
+    const int32_t* __restrict__ offsets, int n_exp, int M, int N, int K, int tail_cus) {
   constexpr int BM = 256, BN = 256, MI = 4, NI = 4;
   constexpr int kATileBytes = BM * kRowBytes;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
@@ -332,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_pipelined_kernel(
   typedef typename Elem16<DT>::vec8 vec8;
 
   TileInfo ti;
-  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti)) return;
+  if (!locate_tile<MODE, BM, BN>(A, B, offsets, n_exp, M, N, K, ti, MODE == 0 ? tail_cus : 0)) return;
   const int kt_count = ti.kt_count;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -523,7 +656,54 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_pipelined_kernel(
   else k_loop(std::false_type{});
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wm, wn, frow, half);
+  // Epilogue through LDS, 64 tile rows (32 of each half of the tile) per pass: the accumulators
+  // (a lane has one row and groups of four columns) are written into a [64][row] buffer and read back
+  // as 16-byte pieces of whole rows, the four wavefronts on neighbouring rows, so that a store
+  // instruction covers one or two contiguous tile rows (a kilobyte) instead of 16 or 32 bytes of each
+  // of 32 rows (alone, that pattern writes at about a third of the rate of whole rows).  Two buffers
+  // alternate: one barrier per pass.
+  __syncthreads();   // every wavefront has read its last fragments: the stages are free
+  constexpr int EB = MODE == 1 ? 4 : 2;            // bytes per output element
+  constexpr int kOutRowB = BN * EB;                // one tile row
+  constexpr int kOutPitch = kOutRowB + 16;
+  constexpr int kOutBuf = 64 * kOutPitch;
+  constexpr int LPR = kOutRowB / 16, RPI = 64 / LPR;   // lanes per row, rows per instruction
+  static_assert(2 * kOutBuf <= lds_bytes(BM, BN), "the two output buffers fit in the stages");
+  unsigned char* outb = static_cast<unsigned char*>(C) +
+      (MODE == 1 ? ((static_cast<int64_t>(ti.expert) * M + ti.m0) * N + ti.col0) * 4
+                 : (static_cast<int64_t>(ti.row0) * N + ti.col0) * 2);
+  const int64_t out_pitch = static_cast<int64_t>(N) * EB;
+  const int cols_b = min(BN, N - ti.col0) * EB;    // valid bytes of a tile row (N is a multiple of 8)
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    unsigned char* buf = lds + (mi & 1) * kOutBuf;
+    unsigned char* wrow = buf + (wm * 32 + frow) * kOutPitch;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = wn * 128 + ni * 32 + q * 8 + half * 4;
+        const float v0 = acc[mi][ni][q * 4 + 0], v1 = acc[mi][ni][q * 4 + 1];
+        const float v2 = acc[mi][ni][q * 4 + 2], v3 = acc[mi][ni][q * 4 + 3];
+        if (MODE == 1) {
+          *reinterpret_cast<float4*>(wrow + col * 4) = make_float4(v0, v1, v2, v3);
+        } else {
+          uint2 p;
+          p.x = Elem16<DT>::pack2(v0, v1);
+          p.y = Elem16<DT>::pack2(v2, v3);
+          *reinterpret_cast<uint2*>(wrow + col * 2) = p;
+        }
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16 / RPI; ++i) {
+      const int lr = (i * 4 + wave) * RPI + lane / LPR;          // row of the buffer
+      const int cb = (lane % LPR) * 16;                          // byte offset in the row
+      const int m = (lr < 32 ? lr : 128 - 32 + lr) + mi * 32;    // row of the tile
+      if (m < ti.rows && cb < cols_b)
+        *reinterpret_cast<u32x4*>(outb + m * out_pitch + cb) = *reinterpret_cast<const u32x4*>(buf + lr * kOutPitch + cb);
+    }
+  }
 }
 #undef PPMOE_BWD_ITER
 #undef PPMOE_BWD_IC
@@ -589,10 +769,18 @@ __global__ __launch_bounds__(256) void act_backward_kernel(const bf16_t* __restr
 
 }  // namespace bwd
 
+// Partial sums of the split-off tails of dX: [splits][local experts][kTailRows][d] float32 (no tail
+// launches with more than 16 local experts: the buffer would grow past what the launches can save).
+static size_t tail_partial_bytes(const moe_config& c) {
+  if (c.local_count > 16) return 0;
+  return static_cast<size_t>(bwd::kTailSplitsMax) * c.local_count * bwd::kTailRows * c.d * sizeof(float);
+}
+
 size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows) {
-  // U, H, dU: three [rows, F] 16-bit buffers (256-byte aligned), then the forward GEMM's scratch
+  // U, H, dU: three [rows, F] 16-bit buffers (256-byte aligned), the forward GEMM's scratch, the
+  // partial sums of dX's tails
   const size_t one = (static_cast<size_t>(rows) * c.F * 2 + 255) & ~size_t(255);
-  return 3 * one + grouped_gemm_workspace_bytes();
+  return 3 * one + ((grouped_gemm_workspace_bytes() + 255) & ~size_t(255)) + tail_partial_bytes(c);
 }
 
 hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
@@ -608,6 +796,7 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   bf16_t* H = reinterpret_cast<bf16_t*>(ws + one);
   bf16_t* dU = reinterpret_cast<bf16_t*>(ws + 2 * one);
   void* gemm_ws = ws + 3 * one;
+  float* tail_partial = reinterpret_cast<float*>(ws + 3 * one + ((grouped_gemm_workspace_bytes() + 255) & ~size_t(255)));
   const int N = c.local_count;
   const bf16_t* xs = static_cast<const bf16_t*>(x_sliced);
   const bf16_t* w1 = static_cast<const bf16_t*>(W1);
@@ -647,6 +836,12 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
       hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(256, 256));
       if (err != hipSuccess) return err;
     }
+    const void* tail[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_tail_kernel<MOE_BF16>),
+                          reinterpret_cast<const void*>(grouped_gemm_bwd_tail_kernel<MOE_F16>)};
+    for (const void* k : tail) {
+      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(kTailRows, 128));
+      if (err != hipSuccess) return err;
+    }
     return hipSuccess;
   });
   if (attrs != hipSuccess) return attrs;
@@ -656,16 +851,16 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
     const int64_t nt = (n_out + bn - 1) / bn;
     return mode == 0 ? ((m_out + bm - 1) / bm + N) * nt : static_cast<int64_t>(N) * ((m_out + bm - 1) / bm) * nt;
   };
-#define PPMOE_BWD(MODE, a, b, cc, m, n, k, m_out)                                                              \
+#define PPMOE_BWD(MODE, a, b, cc, m, n, k, m_out, tail_cus)                                                    \
   do {                                                                                                         \
     const bool big = 2 * tiles_of(MODE, m_out, n, 256, 256) >= n_cus && (MODE == 1 || (k) % BK == 0);          \
     const int t = big ? 256 : 128;                                                                             \
     const unsigned grid = static_cast<unsigned>((tiles_of(MODE, m_out, n, t, t) + 7) / 8 * 8);                 \
     const size_t shm = lds_bytes(t, t);                                                                        \
     if (big && c.in_dtype == MOE_F16)                                                                          \
-      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_F16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);       \
+      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_F16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k, tail_cus); \
     else if (big)                                                                                              \
-      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_BF16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);      \
+      grouped_gemm_bwd_pipelined_kernel<MODE, MOE_BF16><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k, tail_cus); \
     else if (c.in_dtype == MOE_F16)                                                                            \
       grouped_gemm_bwd_kernel<MODE, MOE_F16, 128, 128><<<grid, kThreads, shm, s>>>(a, b, cc, offsets, N, m, n, k);       \
     else                                                                                                       \
@@ -673,7 +868,7 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   } while (0)
 
   // dH = dY B^T  (into the dU buffer), then H = GeLU(U), dU = dH * GeLU'(U) in place
-  PPMOE_BWD(0, dy, w2, dU, 0, c.F, c.d, rows);
+  PPMOE_BWD(0, dy, w2, dU, 0, c.F, c.d, rows, 0);
   {
     const int blocks = static_cast<int>(rows < 256 * 16 ? (rows > 0 ? rows : 1) : 256 * 16);
     if (c.in_dtype == MOE_F16)
@@ -681,11 +876,30 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
     else
       act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
   }
-  // dX = dU A^T
-  PPMOE_BWD(0, dU, w1, dX, 0, c.d, c.F, rows);
+  // dX = dU A^T; with a long contraction the 256 x 256 launch may leave the experts' tail rows to two
+  // small launches of their own (every block of the three takes that decision from the row counts)
+  const bool dx_big = 2 * tiles_of(0, rows, c.d, 256, 256) >= n_cus && c.F % BK == 0;
+  const int tail_cus = (dx_big && c.F >= 4096 && tail_partial_bytes(c) > 0) ? n_cus : 0;
+  PPMOE_BWD(0, dU, w1, dX, 0, c.d, c.F, rows, tail_cus);
+  if (tail_cus > 0) {
+    int splits = c.F / BK / 16;
+    splits = splits < 1 ? 1 : splits > kTailSplitsMax ? kTailSplitsMax : splits;
+    const unsigned tail_grid = static_cast<unsigned>(N * ((c.d + 127) / 128) * splits);
+    if (c.in_dtype == MOE_F16) {
+      grouped_gemm_bwd_tail_kernel<MOE_F16><<<tail_grid, kThreads, lds_bytes(kTailRows, 128), s>>>(
+          dU, w1, tail_partial, offsets, N, c.d, c.F, splits, tail_cus);
+      tail_reduce_kernel<MOE_F16><<<N * kTailRows, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
+                                                                c.d, splits, tail_cus);
+    } else {
+      grouped_gemm_bwd_tail_kernel<MOE_BF16><<<tail_grid, kThreads, lds_bytes(kTailRows, 128), s>>>(
+          dU, w1, tail_partial, offsets, N, c.d, c.F, splits, tail_cus);
+      tail_reduce_kernel<MOE_BF16><<<N * kTailRows, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
+                                                                 c.d, splits, tail_cus);
+    }
+  }
   // dB^T[i] = dY_i^T H_i  ([d, F]);  dA^T[i] = dU_i^T X_i  ([F, d])
-  PPMOE_BWD(1, dy, H, dW2, c.d, c.F, 0, c.d);
-  PPMOE_BWD(1, dU, xs, dW1, c.F, c.d, 0, c.F);
+  PPMOE_BWD(1, dy, H, dW2, c.d, c.F, 0, c.d, 0);
+  PPMOE_BWD(1, dU, xs, dW1, c.F, c.d, 0, c.F, 0);
 #undef PPMOE_BWD
   return hipGetLastError();
 }
