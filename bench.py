@@ -356,7 +356,16 @@ def main():
             detail["backward"] = {"ms_per_call": round(bw_ms, 4),
                                   "gemm_tflops": round(5 * flops_up / (bw_ms * 1e-3) / 1e12, 1),
                                   "ratio_to_forward": round(bw_ms / ms_per_step, 2)}
-            del d_out, dx, dWg, dW1, dW2, bws
+            # The training pair that keeps the forward's intermediates instead of recomputing them.
+            saved = torch.empty(B.moe_layer_saved_bytes(cfg), dtype=torch.uint8, device="cuda")
+            ft_ms = timed(lambda: B.moe_layer_forward_train(cfg, dev["x"], dev["Wg_t"], bias, dev["W1_t"], dev["W2_t"],
+                                                            out, None, None, None, saved, ws), 5)
+            bs_ms = timed(lambda: B.moe_layer_backward_saved(cfg, dev["x"], dev["Wg_t"], dev["W1_t"], dev["W2_t"],
+                                                             d_out, saved, dx, dWg, None, dW1, dW2, bws), 5)
+            detail["backward"].update({"forward_train_ms": round(ft_ms, 4), "backward_saved_ms": round(bs_ms, 4),
+                                       "saved_gemm_tflops": round(4 * flops_up / (bs_ms * 1e-3) / 1e12, 1),
+                                       "train_step_ratio_to_forward": round((ft_ms + bs_ms) / ms_per_step, 2)})
+            del d_out, dx, dWg, dW1, dW2, bws, saved
         except Exception as exc:   # (the backward is not part of the headline number)
             log(f"[bench] backward not measured: {exc!r}")
     log("[bench] " + json.dumps(detail))

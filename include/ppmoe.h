@@ -256,6 +256,29 @@ int moe_layer_backward(const moe_config* cfg, const void* x, const void* Wg, con
                        const void* W2, const void* d_out, void* dx, float* dWg, float* dbias, float* dW1,
                        float* dW2, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Forward and backward of a training step that keeps the forward's intermediates instead of computing
+ * them again (Section 3.2, footnote to Eq. 1: the backward then costs the four gradient products,
+ * twice the forward's two).
+ * moe_layer_forward_train is moe_layer_forward_aux (same `out`, l_aux, mean_prob, first_counts) that
+ * also leaves in `saved` (>= moe_layer_saved_bytes(cfg) bytes of device memory, 16-byte aligned) the
+ * routing (picks, gate weights, offsets, permutation and its inverse, the float32 logits), the
+ * sliced tokens, U = x_sliced A and H = GeLU(U), both in in_dtype.  The activation is applied by a
+ * pass over the stored U, so H, and with it `out`, is rounded once more than in moe_layer_forward.
+ * moe_layer_backward_saved computes what moe_layer_backward computes (same outputs, same formulas)
+ * from `saved` as the forward call with the same cfg, x, Wg, bias, W1 and W2 left it; it reads `saved`
+ * and does not change it.  workspace: moe_workspace_bytes(cfg) for the forward,
+ * moe_layer_backward_workspace_bytes(cfg) for the backward.  in_dtype BF16 or F16 only
+ * (MOE_ERR_DTYPE otherwise; moe_layer_saved_bytes returns 0). */
+size_t moe_layer_saved_bytes(const moe_config* cfg);
+int moe_layer_forward_train(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                            const void* W1, const void* W2, void* out, float* l_aux, float* mean_prob,
+                            int32_t* first_counts, void* saved, size_t saved_bytes, void* workspace,
+                            size_t workspace_bytes, void* stream);
+int moe_layer_backward_saved(const moe_config* cfg, const void* x, const void* Wg, const void* W1,
+                             const void* W2, const void* d_out, const void* saved, size_t saved_bytes, void* dx,
+                             float* dWg, float* dbias, float* dW1, float* dW2, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
 /* Health of the expert-FFN calls that used `workspace` since the last check.  When an output tile
  * is cut between compute units, the partial sums are handed over through the workspace with a
  * bounded wait.  The persistent kernel expects one block per compute unit to be resident at once,

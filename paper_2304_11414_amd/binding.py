@@ -55,6 +55,10 @@ _PROTOTYPES = {
     "moe_expert_ffn_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
     "moe_layer_backward_workspace_bytes": (c_size_t, [POINTER(MoeConfig)]),
     "moe_layer_backward": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
+    "moe_layer_saved_bytes": (c_size_t, [POINTER(MoeConfig)]),
+    "moe_layer_forward_train": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 10 + [c_size_t, c_void_p, c_size_t, c_void_p]),
+    "moe_layer_backward_saved": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 6 + [c_size_t] + [c_void_p] * 6 +
+                                 [c_size_t, c_void_p]),
     "moe_ffn_check": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_int32), c_void_p]),
     "moe_ffn_clock": (c_int, [POINTER(MoeConfig), c_void_p, c_int, POINTER(c_double), POINTER(c_double), c_void_p]),
     "moe_combine": (c_int, [POINTER(MoeConfig)] + [c_void_p] * 5),
@@ -238,6 +242,27 @@ def moe_layer_backward(cfg, x, Wg, bias, W1, W2, d_out, dx, dWg, dbias, dW1, dW2
         byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(d_out), _ptr(dx), _ptr(dWg),
         _ptr(dbias), _ptr(dW1), _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)),
         "moe_layer_backward")
+
+
+def moe_layer_saved_bytes(cfg) -> int:
+    return load_library().moe_layer_saved_bytes(byref(cfg))
+
+
+def moe_layer_forward_train(cfg, x, Wg, bias, W1, W2, out, l_aux, mean_prob, first_counts, saved, workspace,
+                            stream=None):
+    """The layer's forward that keeps in `saved` what moe_layer_backward_saved reads (l_aux, mean_prob,
+    first_counts may be None)."""
+    _check(load_library().moe_layer_forward_train(
+        byref(cfg), _ptr(x), _ptr(Wg), _ptr(bias), _ptr(W1), _ptr(W2), _ptr(out), _ptr(l_aux),
+        _ptr(mean_prob), _ptr(first_counts), _ptr(saved), _nbytes(saved), _ptr(workspace), _nbytes(workspace),
+        _stream(stream)), "moe_layer_forward_train")
+
+
+def moe_layer_backward_saved(cfg, x, Wg, W1, W2, d_out, saved, dx, dWg, dbias, dW1, dW2, workspace, stream=None):
+    _check(load_library().moe_layer_backward_saved(
+        byref(cfg), _ptr(x), _ptr(Wg), _ptr(W1), _ptr(W2), _ptr(d_out), _ptr(saved), _nbytes(saved), _ptr(dx),
+        _ptr(dWg), _ptr(dbias), _ptr(dW1), _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+        "moe_layer_backward_saved")
 
 
 def moe_ffn_check(cfg, workspace, layer_workspace, stream=None) -> int:

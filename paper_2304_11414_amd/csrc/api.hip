@@ -416,6 +416,184 @@ int moe_layer_backward(const moe_config* cfg, const void* x, const void* Wg, con
   return MOE_OK;
 }
 
+static int layer_fuses(const moe_config& c);
+
+namespace {
+
+// What moe_layer_forward_train keeps for moe_layer_backward_saved.
+struct saved_layout {
+  size_t expert_idx, gate_w, offsets, perm, inv_perm, logits, x_sliced, U, H;
+};
+
+void saved_layout_of(const moe_config& c, saved_layout* L, size_t* total) {
+  const size_t tk = static_cast<size_t>(c.T) * c.top_k;
+  const size_t rows = static_cast<size_t>(max_rows_of(c));
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes);
+    return at;
+  };
+  L->expert_idx = take(tk * 4);
+  L->gate_w = take(tk * 4);
+  L->offsets = take(static_cast<size_t>(c.local_count + 1) * 4);
+  L->perm = take(rows * 4);
+  L->inv_perm = take(tk * 4);
+  L->logits = take(static_cast<size_t>(c.T) * c.E * 4);
+  L->x_sliced = take(rows * c.d * 2);
+  L->U = take(rows * c.F * 2);
+  L->H = take(rows * c.F * 2);
+  *total = off;
+}
+
+}  // namespace
+
+size_t moe_layer_saved_bytes(const moe_config* cfg) {
+  if (check_config(cfg) != MOE_OK || !is_16bit(cfg->in_dtype)) return 0;
+  saved_layout S;
+  size_t total = 0;
+  saved_layout_of(*cfg, &S, &total);
+  return total;
+}
+
+int moe_layer_forward_train(const moe_config* cfg, const void* x, const void* Wg, const float* bias,
+                            const void* W1, const void* W2, void* out, float* l_aux, float* mean_prob,
+                            int32_t* first_counts, void* saved, size_t saved_bytes, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (!is_16bit(cfg->in_dtype)) return MOE_ERR_DTYPE;
+  if (x == nullptr || Wg == nullptr || W1 == nullptr || W2 == nullptr || out == nullptr || saved == nullptr ||
+      workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (l_aux == nullptr && (mean_prob != nullptr || first_counts != nullptr)) return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(Wg) || misaligned(bias) || misaligned(W1) || misaligned(W2) ||
+      misaligned(out) || misaligned(saved) || misaligned(workspace) || misaligned(mean_prob) ||
+      misaligned(first_counts) || (reinterpret_cast<uintptr_t>(l_aux) & 3u) != 0)
+    return MOE_ERR_ALIGN;
+  moe_workspace_layout L;
+  saved_layout S;
+  size_t total = 0, saved_total = 0;
+  layout_of(*cfg, &L, &total);
+  saved_layout_of(*cfg, &S, &saved_total);
+  if (workspace_bytes < total || saved_bytes < saved_total) return MOE_ERR_WORKSPACE;
+
+  const moe_config& c = *cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  unsigned char* sv = static_cast<unsigned char*>(saved);
+  int32_t* expert_idx = reinterpret_cast<int32_t*>(sv + S.expert_idx);
+  float* gate_w = reinterpret_cast<float*>(sv + S.gate_w);
+  int32_t* offsets = reinterpret_cast<int32_t*>(sv + S.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(sv + S.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(sv + S.inv_perm);
+  float* logits = reinterpret_cast<float*>(sv + S.logits);
+  void* x_sliced = sv + S.x_sliced;
+  void* U = sv + S.U;
+  void* H = sv + S.H;
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+  int32_t* seg_scratch = reinterpret_cast<int32_t*>(ws + L.scratch);
+  void* y_sliced = ws + L.y_sliced;
+  const int64_t rows = max_rows_of(c);
+#define PPMOE_TRY(expr)                            \
+  do {                                             \
+    if ((expr) != hipSuccess) return MOE_ERR_HIP;  \
+  } while (0)
+  // Gating and permutation as in moe_layer_forward_aux, with the logits written out (the backward's
+  // softmax derivative reads them).
+  const bool want_aux = l_aux != nullptr;
+  const bool fused_gate = gate_is_fused_kernel(c);
+  GateFusion fusion = {};
+  if (fused_gate) {
+    fusion.seg_count = seg_scratch;
+    if (want_aux) {
+      fusion.part_prob = reinterpret_cast<float*>(ws + L.aux);
+      fusion.part_cnt = reinterpret_cast<int32_t*>(fusion.part_prob + static_cast<size_t>(max_segments(c)) * c.E);
+    }
+  }
+  PPMOE_TRY(launch_gate(c, x, Wg, bias, nullptr, logits, expert_idx, gate_w, s, fused_gate ? &fusion : nullptr));
+  if (fusion.seg_assign > 0) {
+    const AuxOut aux = {l_aux, mean_prob, first_counts, fusion.part_prob, fusion.part_cnt, fusion.n_seg, c.E, c.T};
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s,
+                             fusion.seg_assign, true, want_aux ? &aux : nullptr));
+  } else {
+    PPMOE_TRY(launch_permute(c, capacity_of(c), expert_idx, counts, offsets, perm, inv_perm, seg_scratch, s));
+    if (want_aux)
+      PPMOE_TRY(launch_aux_loss(c, logits, expert_idx, l_aux, mean_prob, first_counts, ws + L.aux, s));
+  }
+  // The sliced tokens and both sides of the activation stay for the backward: the first GEMM stores
+  // U = X A, a pass over it H = GeLU(U).
+  PPMOE_TRY(launch_slice(c, x, perm, offsets, x_sliced, rows, s));
+  PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, x_sliced, W1, U, offsets, c.local_count, rows, c.F, c.d,
+                                ws + L.gemm, s));
+  PPMOE_TRY(launch_gelu_rows(c, U, H, offsets, rows, s));
+  const int fuses = layer_fuses(c);
+  if ((fuses & MOE_FUSE_COMBINE) && c.top_k == 1) {
+    if (c.local_count < c.E || c.capacity_factor > 0.f)
+      PPMOE_TRY(launch_zero_unrouted_rows(c, inv_perm, out, s));
+    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, out, offsets, c.local_count, rows, c.d,
+                                  c.F, ws + L.gemm, s, 2, perm, gate_w));
+  } else if (fuses & MOE_FUSE_COMBINE) {
+    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, out, offsets, c.local_count, rows, c.d,
+                                  c.F, ws + L.gemm, s, 2, perm, gate_w, c.top_k, inv_perm, y_sliced));
+    PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s, true));
+  } else {
+    PPMOE_TRY(launch_grouped_gemm(c.in_dtype, false, H, W2, y_sliced, offsets, c.local_count, rows,
+                                  c.d, c.F, ws + L.gemm, s));
+    PPMOE_TRY(launch_combine(c, y_sliced, inv_perm, gate_w, out, s));
+  }
+#undef PPMOE_TRY
+  return MOE_OK;
+}
+
+int moe_layer_backward_saved(const moe_config* cfg, const void* x, const void* Wg, const void* W1,
+                             const void* W2, const void* d_out, const void* saved, size_t saved_bytes, void* dx,
+                             float* dWg, float* dbias, float* dW1, float* dW2, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  int st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (!is_16bit(cfg->in_dtype)) return MOE_ERR_DTYPE;
+  if (x == nullptr || Wg == nullptr || W1 == nullptr || W2 == nullptr || d_out == nullptr || saved == nullptr ||
+      dx == nullptr || dWg == nullptr || dW1 == nullptr || dW2 == nullptr || workspace == nullptr)
+    return MOE_ERR_NULL;
+  if (misaligned(x) || misaligned(Wg) || misaligned(W1) || misaligned(W2) || misaligned(d_out) ||
+      misaligned(saved) || misaligned(dx) || misaligned(dWg) || misaligned(dbias) || misaligned(dW1) ||
+      misaligned(dW2) || misaligned(workspace))
+    return MOE_ERR_ALIGN;
+  backward_layout L;
+  saved_layout S;
+  size_t total = 0, saved_total = 0;
+  backward_layout_of(*cfg, &L, &total);
+  saved_layout_of(*cfg, &S, &saved_total);
+  if (workspace_bytes < total || saved_bytes < saved_total) return MOE_ERR_WORKSPACE;
+
+  const moe_config& c = *cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const unsigned char* sv = static_cast<const unsigned char*>(saved);
+  const int32_t* expert_idx = reinterpret_cast<const int32_t*>(sv + S.expert_idx);
+  const float* gate_w = reinterpret_cast<const float*>(sv + S.gate_w);
+  const int32_t* offsets = reinterpret_cast<const int32_t*>(sv + S.offsets);
+  const int32_t* perm = reinterpret_cast<const int32_t*>(sv + S.perm);
+  const int32_t* inv_perm = reinterpret_cast<const int32_t*>(sv + S.inv_perm);
+  const float* logits = reinterpret_cast<const float*>(sv + S.logits);
+  float* dlogits = reinterpret_cast<float*>(ws + L.dlogits);
+  float* row_dot = reinterpret_cast<float*>(ws + L.row_dot);
+  const int64_t rows = max_rows_of(c);
+#define PPMOE_TRY(expr)                            \
+  do {                                             \
+    if ((expr) != hipSuccess) return MOE_ERR_HIP;  \
+  } while (0)
+  PPMOE_TRY(launch_gather_scale(c, d_out, perm, offsets, gate_w, ws + L.dY, rows, s));
+  PPMOE_TRY(launch_expert_ffn_backward(c, rows, sv + S.x_sliced, offsets, W1, W2, ws + L.dY, ws + L.dX_sliced, dW1,
+                                       dW2, ws + L.ffn, s, row_dot, sv + S.U, sv + S.H));
+  PPMOE_TRY(launch_gate_backward(c, logits, expert_idx, gate_w, inv_perm, row_dot, dlogits, s));
+  PPMOE_TRY(launch_dx(c, ws + L.dX_sliced, inv_perm, dlogits, Wg, dx, s));
+  PPMOE_TRY(launch_dwg(c, x, dlogits, dWg, dbias, ws + L.dwg, s));
+#undef PPMOE_TRY
+  return MOE_OK;
+}
+
 int moe_ffn_check(const moe_config* cfg, const void* workspace, int layer_workspace,
                   int32_t* status, void* stream) {
   int st = check_config(cfg);

@@ -189,7 +189,14 @@ size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows);
 hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
                                       const int32_t* offsets, const void* W1, const void* W2,
                                       const void* dY, void* dX, float* dW1, float* dW2, void* scratch,
-                                      hipStream_t s, float* row_dot = nullptr);
+                                      hipStream_t s, float* row_dot = nullptr, const void* U_saved = nullptr,
+                                      const void* H_saved = nullptr);
+// U_saved, H_saved (both or neither): the pre-activations U = X A and H = GeLU(U) [rows, F] kept by a
+// forward call; then U is not recomputed and H is not written.
+// H = GeLU(U) over the packed rows [0, offsets[n_exp]) x F (16-bit types), the arithmetic of the
+// backward's activation kernel.
+hipError_t launch_gelu_rows(const moe_config& c, const void* U, void* H, const int32_t* offsets, int64_t rows,
+                            hipStream_t s);
 // row_dot (may be nullptr): [rows] float32, row_dot[r] = <dY[r, :], y_sliced[r, :]> (the derivative
 // with respect to a scale factor of row r of the expert output).
 

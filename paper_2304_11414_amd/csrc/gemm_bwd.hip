@@ -713,7 +713,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_pipelined_kernel(
 #undef PPMOE_BWD_WAIT
 #undef PPMOE_BWD_MFMA
 
-// H = GeLU(U) and dU = dH * GeLU'(U) over the packed rows [0, offsets[n_exp]) x F, one row per block
+// H = GeLU(U) (not stored when H is NULL: the caller has it) and dU = dH * GeLU'(U) over the packed
+// rows [0, offsets[n_exp]) x F, one row per block
 // iteration; dH and dU may be the same buffer.  tanh form:  s = 1 / (1 + exp(-2 z)),
 // z = sqrt(2/pi) (u + 0.044715 u^3):   GeLU = u s,   GeLU' = s + 2 u s (1 - s) sqrt(2/pi) (1 + 3 * 0.044715 u^2).
 // row_dot (may be NULL): row_dot[r] = sum_f dH[r, f] * H[r, f], the derivative with respect to a
@@ -753,7 +754,7 @@ __global__ __launch_bounds__(256) void act_backward_kernel(const bf16_t* __restr
         hw[j] = Elem16<DT>::pack2(h[0], h[1]);
         dw[j] = Elem16<DT>::pack2(du[0], du[1]);
       }
-      reinterpret_cast<u32x4*>(H)[at] = u32x4{hw[0], hw[1], hw[2], hw[3]};
+      if (H != nullptr) reinterpret_cast<u32x4*>(H)[at] = u32x4{hw[0], hw[1], hw[2], hw[3]};   // (uniform)
       reinterpret_cast<u32x4*>(dU)[at] = u32x4{dw[0], dw[1], dw[2], dw[3]};
     }
     if (row_dot != nullptr) {   // (uniform)
@@ -767,7 +768,46 @@ __global__ __launch_bounds__(256) void act_backward_kernel(const bf16_t* __restr
   }
 }
 
+// H = GeLU(U) alone, the same arithmetic.
+template <int DT>
+__global__ __launch_bounds__(256) void gelu_rows_kernel(const bf16_t* __restrict__ U, bf16_t* __restrict__ H,
+                                                        const int32_t* __restrict__ offsets, int n_exp, int F) {
+  const int64_t pieces = static_cast<int64_t>(offsets[n_exp]) * (F / 8);   // 16-byte pieces
+  for (int64_t at = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; at < pieces;
+       at += static_cast<int64_t>(gridDim.x) * 256) {
+    const u32x4 u4 = reinterpret_cast<const u32x4*>(U)[at];
+    const uint32_t uw[4] = {u4.x, u4.y, u4.z, u4.w};
+    uint32_t hw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float u[2], h[2];
+      Elem16<DT>::widen2(uw[j], u[0], u[1]);
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const float z2 = 1.5957691216057308f * u[e] * fmaf(0.044715f * u[e], u[e], 1.0f);
+        h[e] = u[e] * (1.0f / (1.0f + __expf(-z2)));
+      }
+      hw[j] = Elem16<DT>::pack2(h[0], h[1]);
+    }
+    reinterpret_cast<u32x4*>(H)[at] = u32x4{hw[0], hw[1], hw[2], hw[3]};
+  }
+}
+
 }  // namespace bwd
+
+hipError_t launch_gelu_rows(const moe_config& c, const void* U, void* H, const int32_t* offsets, int64_t rows,
+                            hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const int64_t pieces = rows * (c.F / 8);
+  const int blocks = static_cast<int>(pieces / 256 < 256 * 16 ? (pieces + 255) / 256 : 256 * 16);
+  if (c.in_dtype == MOE_F16)
+    bwd::gelu_rows_kernel<MOE_F16><<<blocks, 256, 0, s>>>(static_cast<const bf16_t*>(U), static_cast<bf16_t*>(H),
+                                                          offsets, c.local_count, c.F);
+  else
+    bwd::gelu_rows_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(static_cast<const bf16_t*>(U), static_cast<bf16_t*>(H),
+                                                           offsets, c.local_count, c.F);
+  return hipGetLastError();
+}
 
 // Partial sums of the split-off tails of dX: [splits][local experts][kTailRows][d] float32 (no tail
 // launches with more than 16 local experts: the buffer would grow past what the launches can save).
@@ -786,14 +826,16 @@ size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows) {
 hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const void* x_sliced,
                                       const int32_t* offsets, const void* W1, const void* W2,
                                       const void* dY, void* dX, float* dW1, float* dW2, void* scratch,
-                                      hipStream_t s, float* row_dot) {
+                                      hipStream_t s, float* row_dot, const void* U_saved, const void* H_saved) {
   using namespace bwd;
   // (rows == 0: no packed row can exist; every launch below is then empty except the two weight
   // gradients, whose tiles store zeros)
   const size_t one = (static_cast<size_t>(rows) * c.F * 2 + 255) & ~size_t(255);
   unsigned char* ws = static_cast<unsigned char*>(scratch);
-  bf16_t* U = reinterpret_cast<bf16_t*>(ws);
-  bf16_t* H = reinterpret_cast<bf16_t*>(ws + one);
+  const bool saved = U_saved != nullptr && H_saved != nullptr;
+  const bf16_t* U = saved ? static_cast<const bf16_t*>(U_saved) : reinterpret_cast<const bf16_t*>(ws);
+  const bf16_t* H = saved ? static_cast<const bf16_t*>(H_saved) : reinterpret_cast<const bf16_t*>(ws + one);
+  bf16_t* H_out = saved ? nullptr : reinterpret_cast<bf16_t*>(ws + one);
   bf16_t* dU = reinterpret_cast<bf16_t*>(ws + 2 * one);
   void* gemm_ws = ws + 3 * one;
   float* tail_partial = reinterpret_cast<float*>(ws + 3 * one + ((grouped_gemm_workspace_bytes() + 255) & ~size_t(255)));
@@ -803,9 +845,11 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   const bf16_t* w2 = static_cast<const bf16_t*>(W2);
   const bf16_t* dy = static_cast<const bf16_t*>(dY);
 
-  // U = X A (the forward's first GEMM without its activation)
-  hipError_t e = launch_grouped_gemm(c.in_dtype, false, x_sliced, W1, U, offsets, N, rows, c.F, c.d, gemm_ws, s);
-  if (e != hipSuccess) return e;
+  // U = X A (the forward's first GEMM without its activation), unless the forward kept it
+  if (!saved) {
+    hipError_t e = launch_grouped_gemm(c.in_dtype, false, x_sliced, W1, ws, offsets, N, rows, c.F, c.d, gemm_ws, s);
+    if (e != hipSuccess) return e;
+  }
 
   // Tile shape per launch: the pipelined 256 x 256 kernel (one block per CU, half the LDS and L2
   // traffic per flop, latencies hidden by its schedule) unless that leaves more than half of the CUs
@@ -872,9 +916,9 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   {
     const int blocks = static_cast<int>(rows < 256 * 16 ? (rows > 0 ? rows : 1) : 256 * 16);
     if (c.in_dtype == MOE_F16)
-      act_backward_kernel<MOE_F16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
+      act_backward_kernel<MOE_F16><<<blocks, 256, 0, s>>>(U, dU, H_out, dU, row_dot, offsets, N, c.F);
     else
-      act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H, dU, row_dot, offsets, N, c.F);
+      act_backward_kernel<MOE_BF16><<<blocks, 256, 0, s>>>(U, dU, H_out, dU, row_dot, offsets, N, c.F);
   }
   // dX = dU A^T; with a long contraction the 256 x 256 launch may leave the experts' tail rows to two
   // small launches of their own (every block of the three takes that decision from the row counts)

@@ -182,6 +182,33 @@ class DeviceLayer:
         t.cuda.synchronize()
         return dict(dx=to_np(dx), dWg=to_np(dWg), dbias=to_np(dbias), dW1=to_np(dW1), dW2=to_np(dW2))
 
+    def run_train_step(self, d_out):
+        """moe_layer_forward_train, then moe_layer_backward_saved on what it kept; returns (out, l_aux,
+        gradients as run_layer_backward, True if the backward left `saved` as it was)."""
+        t, c = self.torch, self.cfg
+        ws = self.workspace(fill=0xAB)
+        saved = self.empty((B.moe_layer_saved_bytes(c),), t.uint8)
+        saved.fill_(0xCD)
+        out = self.empty((c.T, c.d), torch_dtype(self.lc.out_dtype))
+        out.fill_(7.0)
+        l_aux = t.full((1,), -1.0, dtype=t.float32, device="cuda")
+        B.moe_layer_forward_train(c, self.x, self.Wg, self.bias, self.W1, self.W2, out, l_aux, None, None, saved, ws)
+        assert B.moe_ffn_check(c, ws, True) == 0, "a hand-over of partial sums did not arrive"
+        before = saved.clone()
+        do = to_dev(np.asarray(d_out, dtype=np.float32), self.lc.out_dtype)
+        dx = self.empty((c.T, c.d), torch_dtype(self.lc.in_dtype))
+        dWg = t.full((c.E, c.d), 7.0, dtype=t.float32, device="cuda")
+        dbias = t.full((c.E,), 7.0, dtype=t.float32, device="cuda")
+        dW1 = t.full((c.local_count, c.F, c.d), 7.0, dtype=t.float32, device="cuda")
+        dW2 = t.full((c.local_count, c.d, c.F), 7.0, dtype=t.float32, device="cuda")
+        bws = self.empty((B.moe_layer_backward_workspace_bytes(c),), t.uint8)
+        bws.fill_(0xAB)
+        B.moe_layer_backward_saved(c, self.x, self.Wg, self.W1, self.W2, do, saved, dx, dWg, dbias, dW1, dW2, bws)
+        t.cuda.synchronize()
+        untouched = bool(t.equal(saved, before))
+        grads = dict(dx=to_np(dx), dWg=to_np(dWg), dbias=to_np(dbias), dW1=to_np(dW1), dW2=to_np(dW2))
+        return to_np(out), float(l_aux.item()), grads, untouched
+
     def run_combine(self, y_sliced, inv_perm, gate_w):
         t, c = self.torch, self.cfg
         y = self.empty((max(self.rows, 1), c.d), torch_dtype(self.lc.in_dtype))

@@ -502,6 +502,22 @@ def test_layer_backward(kw):
     if none_kept.any():
         assert_close(got["dx"][none_kept], ref["dx_gate"][none_kept], tol, "dx of unrouted tokens", et)
 
+    # The same step with the forward's intermediates kept (moe_layer_forward_train, then
+    # moe_layer_backward_saved): the layer output and the balance loss of the forward, the same
+    # gradients from what it kept, and the kept state left as it was.
+    out, l_aux, kept, untouched = DeviceLayer(lc, inp).run_train_step(d_out)
+    assert untouched, "moe_layer_backward_saved wrote into the saved state"
+    # (U is stored in the 16-bit type before the activation: `out` rests on three roundings like the
+    # gradients, not two like moe_layer_forward's, so its elementwise bound is the gradients')
+    assert_close(out, ref["fwd"]["out"], tol, "out (train)", et)
+    ref_aux = O.aux_loss(ref["fwd"]["logits"], ref["fwd"]["expert_idx"])
+    assert abs(l_aux - ref_aux["l_aux"]) <= AUX_TOL * abs(ref_aux["l_aux"]), (l_aux, ref_aux["l_aux"])
+    assert_close(kept["dW2"], ref["dW2"].transpose(0, 2, 1), tol, "dW2 (saved)", et)
+    assert_close(kept["dW1"], ref["dW1"].transpose(0, 2, 1), tol, "dW1 (saved)", et)
+    assert_close(kept["dWg"], ref["dWg"].T, tol, "dWg (saved)", et)
+    assert_close(kept["dbias"], ref["dbias"], tol, "dbias (saved)", et)
+    assert_close(kept["dx"], ref["dx"], tol, "dx (saved)", et)
+
 
 def test_layer_backward_headline_size():
     """moe_layer_backward at the headline workload's full size, in the launch configuration the
