@@ -489,7 +489,8 @@ def test_layer_backward(kw):
     ref = O.layer_backward(inp["x"], mv["Wg"], inp["bias"], mv["W1"], mv["W2"], d_out, E=lc.E, k=lc.top_k,
                            local_begin=lc.local_begin, local_count=lc.n_local,
                            capacity_factor=lc.capacity_factor, renorm=lc.renorm_topk)
-    got = DeviceLayer(lc, inp).run_layer_backward(d_out)
+    layer = DeviceLayer(lc, inp)
+    got = layer.run_layer_backward(d_out)
     tol = TOL[lc.in_dtype]
     et = GRAD_ELEM_FACTOR * tol
     assert_close(got["dW2"], ref["dW2"].transpose(0, 2, 1), tol, "dW2", et)
@@ -505,7 +506,8 @@ def test_layer_backward(kw):
     # The same step with the forward's intermediates kept (moe_layer_forward_train, then
     # moe_layer_backward_saved): the layer output and the balance loss of the forward, the same
     # gradients from what it kept, and the kept state left as it was.
-    out, l_aux, kept, untouched = DeviceLayer(lc, inp).run_train_step(d_out)
+    del got
+    out, l_aux, kept, untouched = layer.run_train_step(d_out)
     assert untouched, "moe_layer_backward_saved wrote into the saved state"
     # (U is stored in the 16-bit type before the activation: `out` rests on three roundings like the
     # gradients, not two like moe_layer_forward's, so its elementwise bound is the gradients')
