@@ -229,7 +229,7 @@ int moe_expert_ffn(const moe_config* cfg, const void* x_sliced, const int32_t* o
  * in_dtype BF16 or F16 only (MOE_ERR_DTYPE otherwise).  x_sliced, dY, dX_sliced: [moe_max_rows, d];
  * rows at or beyond offsets[local_count] are neither read nor written.
  * workspace: at least moe_ffn_backward_workspace_bytes(cfg) bytes of device scratch (three
- * [moe_max_rows, F] buffers, the expert GEMM's own scratch and, with at most 16 local experts, 4096 * d
+ * [moe_max_rows, F] buffers, the expert GEMM's own scratch and, with at most 16 local experts, 8192 * d
  * bytes per local expert of float32 partial sums for the experts' last rows of dX_sliced); the first
  * expert-FFN call of a device may synchronise once, see moe_init. */
 size_t moe_ffn_backward_workspace_bytes(const moe_config* cfg);

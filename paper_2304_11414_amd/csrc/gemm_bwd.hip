@@ -21,7 +21,7 @@
 // row).  Weight gradients are float32 (the precision gradients are accumulated in); data gradients
 // have the layer's 16-bit type.  Sums have a fixed order: bitwise reproducible.  Where the data
 // gradient's contraction is long, the experts' last few rows may leave the 256 x 256 launch for a
-// split-contraction launch of their own (tails_split_off below).
+// split-contraction launch of their own (tail_threshold below).
 
 #include <type_traits>
 
@@ -122,30 +122,48 @@ struct TileInfo {
   Operand opA, opB;   // opA: the operand whose tile rows are the output rows; opB: the output columns
 };
 
-// Data gradient with a long contraction: an expert's last rows, when they are at most kTailRows past a
-// multiple of 256, cost the 256 x 256 kernel a whole tile each, and with few tiles per CU a whole
-// extra round of the chip.  They can go to a second launch instead (128-row tiles, the contraction
-// split over several blocks, partial sums added up in a fixed order by a third launch).  Every block
-// of the three launches takes that decision from the row counts alone, so they all agree:
-// tails are split off when that saves the 256 x 256 launch a round and the tail tiles are cheap enough.
-constexpr int kTailRows = 128;
+// Data gradient with a long contraction: an expert's rows past the last multiple of 256 cost the
+// 256 x 256 kernel a whole tile each, and with few tiles per CU a whole extra round of the chip.
+// They can go to a second launch instead (128-row tiles, 32-row blocks without a valid row skipped,
+// the contraction split over several blocks, partial sums added up in a fixed order by a third
+// launch).  Every block of the three launches takes that decision from the row counts alone, so they
+// all agree.  tail_threshold returns t: remainders of 1..t rows are split off (0: none).  The smaller
+// candidate (128) is taken if it saves the 256 x 256 launch at least as much as the larger would;
+// a candidate qualifies when what it saves (whole rounds when there are few, else the tiles'
+// share of a round) outweighs the tail launch, which runs at about a third of the rate per flop.
+constexpr int kTailTile = 128;        // row tile of the tail launch
 constexpr int kTailSplitsMax = 8;
-__device__ __forceinline__ int tail_rows_of(int n) {
+__device__ __forceinline__ int tail_rows_of(int n, int threshold) {
   const int t = n & 255;
-  return (t > 0 && t <= kTailRows) ? t : 0;
+  return t <= threshold ? t : 0;
 }
-__device__ __forceinline__ bool tails_split_off(const int32_t* __restrict__ offsets, int n_exp, int N, int tail_cus) {
-  if (tail_cus <= 0) return false;   // (the launcher has not provided for the two extra launches)
+__device__ __forceinline__ int tail_threshold(const int32_t* __restrict__ offsets, int n_exp, int N, int tail_cus) {
+  if (tail_cus <= 0) return 0;   // (the launcher has not provided for the two extra launches)
   const int n_tiles = (N + 255) / 256;
-  int all = 0, big = 0, tails = 0;
+  int all = 0, big[2] = {0, 0}, blocks[2] = {0, 0};   // candidates 128 and 255
   for (int i = 0; i < n_exp; ++i) {
-    const int n = offsets[i + 1] - offsets[i], t = tail_rows_of(n);
+    const int n = offsets[i + 1] - offsets[i];
     all += (n + 255) / 256 * n_tiles;
-    big += (n - t + 255) / 256 * n_tiles;
-    tails += t > 0;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int t = tail_rows_of(n, c == 0 ? 128 : 255);
+      big[c] += (n - t + 255) / 256 * n_tiles;
+      blocks[c] += (t + 31) / 32;
+    }
   }
-  const int rounds_all = (all + tail_cus - 1) / tail_cus, rounds_big = (big + tail_cus - 1) / tail_cus;
-  return rounds_big < rounds_all && tails * N <= 24576;
+  const int rounds_all = (all + tail_cus - 1) / tail_cus;
+  int saved[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    // in units of a 32-row block of one 256-column tile: a tile is 8 of them
+    const int rounds = (big[c] + tail_cus - 1) / tail_cus;
+    const int64_t saving = 8 * (rounds_all <= 4 ? static_cast<int64_t>(rounds_all - rounds) * tail_cus
+                                                : static_cast<int64_t>(all - big[c]));
+    const int64_t cost = 3 * static_cast<int64_t>(blocks[c]) * n_tiles;
+    saved[c] = (all > big[c] && cost <= saving) ? static_cast<int>(saving - cost) + 1 : 0;
+  }
+  if (saved[0] > 0 && saved[0] >= saved[1]) return 128;
+  return saved[1] > 0 ? 255 : 0;
 }
 
 // tail_cus (MODE 0 only): 0, or the number of CUs when the launcher runs the tail launches as well.
@@ -164,11 +182,11 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
   };
   if (MODE == 0) {
     // tiles ordered expert-major, then n-tile, then m-tile; blocks past the last tile leave
-    const bool no_tails = tails_split_off(offsets, n_exp, N, tail_cus);
+    const int tail_thr = tail_threshold(offsets, n_exp, N, tail_cus);
     int total = 0;
     for (int i = 0; i < n_exp; ++i) {
       const int n = offsets[i + 1] - offsets[i];
-      total += (n - (no_tails ? tail_rows_of(n) : 0) + BM - 1) / BM * n_tiles;
+      total += (n - tail_rows_of(n, tail_thr) + BM - 1) / BM * n_tiles;
     }
     int tile = xcd_tile(blockIdx.x, total);
     if (tile < 0) return false;
@@ -176,7 +194,7 @@ __device__ __forceinline__ bool locate_tile(const bf16_t* __restrict__ A, const 
     int lo = offsets[0];
     for (int i = 0; i < n_exp && !found; ++i) {
       const int next = offsets[i + 1];
-      const int hi = next - (no_tails ? tail_rows_of(next - lo) : 0);
+      const int hi = next - tail_rows_of(next - lo, tail_thr);
       const int m_tiles = (hi - lo + BM - 1) / BM;
       const int here = m_tiles * n_tiles;
       if (tile < here) {
@@ -346,32 +364,35 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_kernel(
   store_tile_output<MODE, DT, BM, BN>(acc, C, ti, N, M, wave >> 1, wave & 1, lane & 31, lane >> 5);
 }
 
-// The split-off tails of the data gradient (see tails_split_off): block (expert, column tile, split)
-// multiplies the expert's tail rows (at most kTailRows) by a 128-column panel over its share of the
-// contraction and leaves float32 partial sums in `partial` [splits][n_exp][kTailRows][N].
+// The split-off tails of the data gradient (see tail_threshold): block (expert, row tile, column tile,
+// split) multiplies up to 128 of the expert's tail rows by a 128-column panel over its share of the
+// contraction and leaves float32 partial sums in `partial` [splits][n_exp][256][N].
 template <int DT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_tail_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, float* __restrict__ partial,
     const int32_t* __restrict__ offsets, int n_exp, int N, int K, int splits, int tail_cus) {
-  constexpr int BM = kTailRows, BN = 128;
+  constexpr int BM = kTailTile, BN = 128;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  if (!tails_split_off(offsets, n_exp, N, tail_cus)) return;
+  const int tail_thr = tail_threshold(offsets, n_exp, N, tail_cus);
+  if (tail_thr == 0) return;
   const int n_tiles = (N + BN - 1) / BN;
   int b = blockIdx.x;
   const int nt = b % n_tiles;
   b /= n_tiles;
-  const int split = b % splits, expert = b / splits;
+  const int split = b % splits;
+  b /= splits;
+  const int rt = b & 1, expert = b >> 1;
   const int lo = offsets[expert], hi = offsets[expert + 1];
-  const int tail = tail_rows_of(hi - lo);
-  if (tail == 0) return;
+  const int tail = tail_rows_of(hi - lo, tail_thr);
+  if (rt * BM >= tail) return;
   TileInfo ti;
   ti.expert = expert;
-  ti.row0 = hi - tail;
-  ti.rows = tail;
+  ti.row0 = hi - tail + rt * BM;
+  ti.rows = min(BM, tail - rt * BM);
   ti.col0 = nt * BN;
   ti.m0 = 0;
   ti.kt_count = (K + BK - 1) / BK;
-  ti.opA = Operand{A + static_cast<int64_t>(ti.row0) * K, K, tail, K};
+  ti.opA = Operand{A + static_cast<int64_t>(ti.row0) * K, K, ti.rows, K};
   ti.opB = Operand{B + static_cast<int64_t>(expert) * K * N + ti.col0, N, min(BN, N - ti.col0), K};
   const int per = (ti.kt_count + splits - 1) / splits;
   const int kt_begin = split * per, kt_end = min(ti.kt_count, kt_begin + per);
@@ -381,12 +402,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_bwd_tail_kernel(
   // lane: row frow of each 32-row block; register v: column (v / 4) * 8 + half * 4 + v % 4
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1, frow = lane & 31, half = lane >> 5;
-  float* out = partial + (static_cast<int64_t>(split) * n_exp + expert) * kTailRows * N;
+  float* out = partial + ((static_cast<int64_t>(split) * n_exp + expert) * 256 + rt * BM) * N;
   const int cols = min(BN, N - ti.col0);
 #pragma unroll
   for (int mi = 0; mi < BM / 64; ++mi) {
     const int m = wm * (BM / 2) + mi * 32 + frow;
-    if (m >= tail) continue;
+    if (m >= ti.rows) continue;
 #pragma unroll
     for (int ni = 0; ni < BN / 64; ++ni)
 #pragma unroll
@@ -405,16 +426,17 @@ template <int DT>
 __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
                                                           const int32_t* __restrict__ offsets, int n_exp, int N,
                                                           int splits, int tail_cus) {
-  if (!tails_split_off(offsets, n_exp, N, tail_cus)) return;
-  const int expert = blockIdx.x / kTailRows, r = blockIdx.x % kTailRows;
+  const int tail_thr = tail_threshold(offsets, n_exp, N, tail_cus);
+  if (tail_thr == 0) return;
+  const int expert = blockIdx.x >> 8, r = blockIdx.x & 255;
   const int lo = offsets[expert], hi = offsets[expert + 1];
-  const int tail = tail_rows_of(hi - lo);
+  const int tail = tail_rows_of(hi - lo, tail_thr);
   if (r >= tail) return;
   bf16_t* crow = C + static_cast<int64_t>(hi - tail + r) * N;
   for (int n = threadIdx.x * 8; n < N; n += 256 * 8) {   // (N is a multiple of 8)
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int sp = 0; sp < splits; ++sp) {
-      const float* p = partial + ((static_cast<int64_t>(sp) * n_exp + expert) * kTailRows + r) * N + n;
+      const float* p = partial + ((static_cast<int64_t>(sp) * n_exp + expert) * 256 + r) * N + n;
       const float4 u = *reinterpret_cast<const float4*>(p), w = *reinterpret_cast<const float4*>(p + 4);
       a[0] += u.x; a[1] += u.y; a[2] += u.z; a[3] += u.w;
       a[4] += w.x; a[5] += w.y; a[6] += w.z; a[7] += w.w;
@@ -809,11 +831,11 @@ hipError_t launch_gelu_rows(const moe_config& c, const void* U, void* H, const i
   return hipGetLastError();
 }
 
-// Partial sums of the split-off tails of dX: [splits][local experts][kTailRows][d] float32 (no tail
+// Partial sums of the split-off tails of dX: [splits][local experts][256][d] float32 (no tail
 // launches with more than 16 local experts: the buffer would grow past what the launches can save).
 static size_t tail_partial_bytes(const moe_config& c) {
   if (c.local_count > 16) return 0;
-  return static_cast<size_t>(bwd::kTailSplitsMax) * c.local_count * bwd::kTailRows * c.d * sizeof(float);
+  return static_cast<size_t>(bwd::kTailSplitsMax) * c.local_count * 256 * c.d * sizeof(float);
 }
 
 size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows) {
@@ -883,7 +905,7 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
     const void* tail[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_tail_kernel<MOE_BF16>),
                           reinterpret_cast<const void*>(grouped_gemm_bwd_tail_kernel<MOE_F16>)};
     for (const void* k : tail) {
-      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(kTailRows, 128));
+      hipError_t err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(kTailTile, 128));
       if (err != hipSuccess) return err;
     }
     return hipSuccess;
@@ -928,16 +950,16 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   if (tail_cus > 0) {
     int splits = c.F / BK / 16;
     splits = splits < 1 ? 1 : splits > kTailSplitsMax ? kTailSplitsMax : splits;
-    const unsigned tail_grid = static_cast<unsigned>(N * ((c.d + 127) / 128) * splits);
+    const unsigned tail_grid = static_cast<unsigned>(N * 2 * ((c.d + 127) / 128) * splits);
     if (c.in_dtype == MOE_F16) {
-      grouped_gemm_bwd_tail_kernel<MOE_F16><<<tail_grid, kThreads, lds_bytes(kTailRows, 128), s>>>(
+      grouped_gemm_bwd_tail_kernel<MOE_F16><<<tail_grid, kThreads, lds_bytes(kTailTile, 128), s>>>(
           dU, w1, tail_partial, offsets, N, c.d, c.F, splits, tail_cus);
-      tail_reduce_kernel<MOE_F16><<<N * kTailRows, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
+      tail_reduce_kernel<MOE_F16><<<N * 256, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
                                                                 c.d, splits, tail_cus);
     } else {
-      grouped_gemm_bwd_tail_kernel<MOE_BF16><<<tail_grid, kThreads, lds_bytes(kTailRows, 128), s>>>(
+      grouped_gemm_bwd_tail_kernel<MOE_BF16><<<tail_grid, kThreads, lds_bytes(kTailTile, 128), s>>>(
           dU, w1, tail_partial, offsets, N, c.d, c.F, splits, tail_cus);
-      tail_reduce_kernel<MOE_BF16><<<N * kTailRows, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
+      tail_reduce_kernel<MOE_BF16><<<N * 256, 256, 0, s>>>(tail_partial, static_cast<bf16_t*>(dX), offsets, N,
                                                                  c.d, splits, tail_cus);
     }
   }

@@ -302,11 +302,12 @@ def test_handover_that_never_arrives_is_recomputed(d, F, counts):
     # k-tiles (17 and 33), partial column tiles, experts of 0, 1 and 65 rows, ragged contraction lengths
     ("bf16", 1088, 2112, [700, 0, 1, 2500, 65, 2800]),
     ("f16", 576, 4160, [300, 1500, 31, 0, 2000]),
-    # long contraction for dX (F >= 4096): the experts' tail rows (at most 128 past a multiple of 256)
-    # leave the 256 x 256 launch for the split-contraction tail launches when that saves a round --
-    # 16 full row tiles x 16 column tiles fill the 256 CUs once, tails of 3, 100, 128 and 1 rows; then
-    # tails only (no 256-row tile at all)
-    ("bf16", 4096, 4096, [1027, 612, 256, 1408, 1025, 0]),
+    # long contraction for dX (F >= 4096): the experts' rows past a multiple of 256 leave the
+    # 256 x 256 launch for the split-contraction tail launches when that saves a round -- 16 full row
+    # tiles x 16 column tiles fill the 256 CUs once, remainders of 3, 188, 128 and 176 rows (one or two
+    # 128-row tail tiles each: only splitting off all of them saves the round); then short tails only
+    # (no 256-row tile at all, remainders up to 128 suffice)
+    ("bf16", 4096, 4096, [1027, 700, 256, 1408, 1200, 0]),
     ("f16", 4096, 4096, [100, 128, 1, 0, 64, 37]),
 ])
 def test_expert_ffn_backward_on_oracle_rows(dtype, d, F, counts):
