@@ -553,6 +553,36 @@ def test_layer_is_bitwise_reproducible_and_ignores_workspace_contents():
     assert bool((a.view(dl.torch.int16) == b.view(dl.torch.int16)).all())
 
 
+def test_backward_is_bitwise_reproducible():
+    """Every sum of the backward has a fixed order (no atomics; partial sums of cut contractions and of
+    token chunks are added in index order): two runs give the same bits.  A layer backward, the train
+    step's backward from kept intermediates, and an expert-FFN backward in the configuration with the
+    256 x 256 kernels and the split-contraction tail launches."""
+    lc = small_cfg(T=1500, d=256, F=512, E=8, top_k=2, renorm_topk=True, seed=33)
+    inp = synth.make_inputs(lc)
+    dl = DeviceLayer(lc, inp)
+    d_out = np.random.default_rng(7).standard_normal((lc.T, lc.d)).astype(np.float32)
+    a, b = dl.run_layer_backward(d_out), dl.run_layer_backward(d_out)
+    for name in a:
+        np.testing.assert_array_equal(a[name], b[name], err_msg=name)
+    _, _, c, _ = dl.run_train_step(d_out)
+    _, _, e, _ = dl.run_train_step(d_out)
+    for name in c:
+        np.testing.assert_array_equal(c[name], e[name], err_msg=name + " (saved)")
+
+    counts = [1027, 700, 256, 1408, 1200, 0]
+    n = len(counts)
+    A = int(sum(counts))
+    lc2 = small_cfg(T=A, d=4096, F=4096, E=n, top_k=1, seed=35)   # (16 x 16 + 4 x 16 tiles: the tails go)
+    inp2 = synth.make_inputs(lc2, parts=("x", "W1_t", "W2_t"))
+    dY = np.random.default_rng(8).standard_normal((A, lc2.d)).astype(np.float32)
+    dl2 = DeviceLayer(lc2, inp2)
+    r1 = dl2.run_ffn_backward(inp2["x"], ragged_offsets(counts), dY)
+    r2 = dl2.run_ffn_backward(inp2["x"], ragged_offsets(counts), dY)
+    for u, v, name in zip(r1, r2, ("dX", "dW1", "dW2")):
+        np.testing.assert_array_equal(u, v, err_msg=name)
+
+
 def test_layer_replays_from_a_hip_graph():
     """moe_layer_forward neither allocates nor synchronises, so it can be captured: the captured
     layer is replayed several times, with the program's own eager work and synchronisations between
