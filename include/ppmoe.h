@@ -267,7 +267,8 @@ int moe_layer_backward(const moe_config* cfg, const void* x, const void* Wg, con
  * pass over the stored U, so H, and with it `out`, is rounded once more than in moe_layer_forward.
  * moe_layer_backward_saved computes what moe_layer_backward computes (same outputs, same formulas)
  * from `saved` as the forward call with the same cfg, x, Wg, bias, W1 and W2 left it; it reads `saved`
- * and does not change it.  workspace: moe_workspace_bytes(cfg) for the forward,
+ * and does not change it.  Neither call allocates or synchronises: a step can be captured into a
+ * HIP graph (after one eager call, which sets kernel attributes).  workspace: moe_workspace_bytes(cfg) for the forward,
  * moe_layer_backward_workspace_bytes(cfg) for the backward.  in_dtype BF16 or F16 only
  * (MOE_ERR_DTYPE otherwise; moe_layer_saved_bytes returns 0). */
 size_t moe_layer_saved_bytes(const moe_config* cfg);

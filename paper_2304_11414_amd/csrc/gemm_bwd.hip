@@ -838,6 +838,19 @@ static size_t tail_partial_bytes(const moe_config& c) {
   return static_cast<size_t>(bwd::kTailSplitsMax) * c.local_count * 256 * c.d * sizeof(float);
 }
 
+// Compute units of the current device (asked once per device: the launcher may run under stream capture).
+static int cus_of_current_device() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int cus = cached[dev].load(std::memory_order_relaxed);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cached[dev].store(cus, std::memory_order_relaxed);
+  }
+  return cus;
+}
+
 size_t expert_ffn_backward_scratch_bytes(const moe_config& c, int64_t rows) {
   // U, H, dU: three [rows, F] 16-bit buffers (256-byte aligned), the forward GEMM's scratch, the
   // partial sums of dX's tails
@@ -877,13 +890,7 @@ hipError_t launch_expert_ffn_backward(const moe_config& c, int64_t rows, const v
   // traffic per flop, latencies hidden by its schedule) unless that leaves more than half of the CUs
   // without a tile; then 128 x 128 (two blocks per CU, compiler-scheduled; also K not a multiple of
   // 64).  The host knows the row count only as a bound (the counts live on the device).
-  int n_cus = 256;
-  {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      n_cus = prop.multiProcessorCount;
-  }
+  const int n_cus = cus_of_current_device();
   static std::atomic<uint64_t> attrs_done{0};
   const hipError_t attrs = once_per_device(attrs_done, [] {
     const void* small[] = {reinterpret_cast<const void*>(grouped_gemm_bwd_kernel<0, MOE_BF16, 128, 128>),

@@ -13,7 +13,7 @@ from oracle import ppmoe_oracle as O
 from paper_2304_11414_amd import synth
 from paper_2304_11414_amd.synth import LayerConfig
 from tests.conftest import read_golden
-from tests.gpu_util import GRAD_ELEM_FACTOR, TOL, DeviceLayer, assert_close, max_rel_err, to_np
+from tests.gpu_util import GRAD_ELEM_FACTOR, TOL, DeviceLayer, assert_close, max_rel_err, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -614,6 +614,53 @@ def test_layer_replays_from_a_hip_graph():
         assert B.moe_ffn_check(c, ws, True) == 0
         again, _ = dl.run_layer(ws_fill=rep)       # eager work between the replays
         assert bool((again.view(torch.int16) == eager.view(torch.int16)).all())
+
+
+def test_train_step_replays_from_a_hip_graph():
+    """moe_layer_forward_train + moe_layer_backward_saved captured together (neither allocates nor
+    synchronises): replays, with eager work between them, give the eager step's bits."""
+    import torch
+    from paper_2304_11414_amd import binding as B
+    lc = small_cfg(T=1500, d=256, F=4096, E=8, top_k=2, renorm_topk=True, seed=43)
+    inp = synth.make_inputs(lc)
+    dl = DeviceLayer(lc, inp)
+    d_out = np.random.default_rng(9).standard_normal((lc.T, lc.d)).astype(np.float32)
+    eager_out, _, eager, _ = dl.run_train_step(d_out)          # also the library's one-time set-up
+    c = dl.cfg
+    ws = dl.workspace(fill=0x5A)
+    bws = torch.empty(B.moe_layer_backward_workspace_bytes(c), dtype=torch.uint8, device="cuda")
+    saved = torch.empty(B.moe_layer_saved_bytes(c), dtype=torch.uint8, device="cuda")
+    do = to_dev(d_out, lc.out_dtype)
+    out = torch.empty((lc.T, lc.d), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((lc.T, lc.d), dtype=torch.bfloat16, device="cuda")
+    dWg = torch.empty((lc.E, lc.d), dtype=torch.float32, device="cuda")
+    dbias = torch.empty((lc.E,), dtype=torch.float32, device="cuda")
+    dW1 = torch.empty((lc.n_local, lc.F, lc.d), dtype=torch.float32, device="cuda")
+    dW2 = torch.empty((lc.n_local, lc.d, lc.F), dtype=torch.float32, device="cuda")
+
+    def step():
+        B.moe_layer_forward_train(c, dl.x, dl.Wg, dl.bias, dl.W1, dl.W2, out, None, None, None, saved, ws)
+        B.moe_layer_backward_saved(c, dl.x, dl.Wg, dl.W1, dl.W2, do, saved, dx, dWg, dbias, dW1, dW2, bws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                                   # warm the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (out, dx, dWg, dbias, dW1, dW2):
+            t.fill_(3.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(to_np(out), eager_out, err_msg=f"out, replay {rep}")
+        for name, t in (("dx", dx), ("dWg", dWg), ("dbias", dbias), ("dW1", dW1), ("dW2", dW2)):
+            np.testing.assert_array_equal(to_np(t), eager[name], err_msg=f"{name}, replay {rep}")
+        assert B.moe_ffn_check(c, ws, True) == 0
+        dl.run_layer(ws_fill=rep)                                # eager work between the replays
 
 
 FIRST_CALL_CAPTURE = r"""
